@@ -1,0 +1,136 @@
+/*
+ * fk — budgeted KV-cache decoding with learned eviction (ForesightKV generation path)
+ * for AMD MI355X (gfx950).  C ABI; every kernel behind it is hand-written HIP.
+ *
+ * The path (Section 3.1 of the paper, "Dynamic KV Cache Eviction During Long-Context
+ * Generation"): the cache holds at most B + L pairs per (sequence, KV head).  Every
+ * decode step appends the new pair (fk_append) and attends over the retained pairs
+ * (fk_decode_attn).  After every L steps the retained pairs are scored by an MLP
+ * (fk_score_kv), the L newest plus the B - L most important others are selected
+ * (fk_select_keep) and the cache is compacted back to B entries (fk_compact).
+ *
+ * Memory layout (row major, all DEVICE memory owned by the caller):
+ *   K, V   [batch][n_kv_heads][capacity][head_dim]   dtype (fp32 or bf16)
+ *   pos    [batch][n_kv_heads][capacity]             int32 absolute position of each slot
+ *   len    [batch]                                   int32 retained count (equal for all KV heads)
+ * A (sequence, KV head) pair is called a row.  Slots 0 .. len[b]-1 of a row are live.
+ * Precondition kept by fk_append and fk_compact: along the live slots of a row the
+ * positions are strictly increasing, so slot order is position order.
+ *
+ * Conventions:
+ *   - descriptor structs are HOST memory, read during the call only;
+ *   - all other pointers are DEVICE pointers, 16-byte aligned, owned by the caller;
+ *   - `stream` is a hipStream_t passed as void* (NULL = the null stream); every call
+ *     only enqueues work on it and returns; nothing is allocated, no state is kept;
+ *   - errors are return codes; arguments are validated on the host before any launch;
+ *   - `max_len` is a host-side upper bound on every len[b] at the time the kernels run
+ *     (pass `capacity` when unknown); it only sizes the launch.
+ *   - supported: head_dim 64 or 128; dtype fp32 or bf16; n_q_heads a multiple of
+ *     n_kv_heads with group size <= 8; capacity < 2^24.
+ */
+#ifndef FK_H
+#define FK_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    FK_OK = 0,
+    FK_ERR_INVALID_ARG = 1, /* null pointer, non-positive size, inconsistent sizes */
+    FK_ERR_UNSUPPORTED = 2, /* shape or dtype outside the supported set */
+    FK_ERR_WORKSPACE = 3,   /* workspace missing or too small */
+    FK_ERR_LAUNCH = 4       /* the HIP runtime refused a launch */
+} fk_status;
+
+typedef enum { FK_F32 = 0, FK_BF16 = 1 } fk_dtype;
+
+typedef struct {
+    int32_t batch;      /* sequences */
+    int32_t n_q_heads;  /* query heads per sequence */
+    int32_t n_kv_heads; /* KV heads per sequence; group size g = n_q_heads / n_kv_heads */
+    int32_t head_dim;   /* D */
+    int32_t capacity;   /* slots per row, >= B + L */
+    int32_t dtype;      /* fk_dtype of q, K, V, out and of the scorer's W1 */
+} fk_cache_desc;
+
+/* Scoring model of one layer (Appendix B.1): phi = gelu(x W1 + b1) W2 + b2, x = concat(k, v). */
+typedef struct {
+    const void *w1;   /* device [n_sets][2*head_dim][hidden], cache dtype */
+    const float *b1;  /* device [n_sets][hidden] */
+    const float *w2;  /* device [n_sets][hidden] */
+    const float *b2;  /* device [n_sets] */
+    int32_t hidden;   /* H; bf16: multiple of 32 with H*(2*head_dim+8)*2 + 8*H <= 160 KiB of LDS */
+    int32_t per_head; /* 1: n_sets = n_kv_heads, one model per KV head; 0: one shared model */
+} fk_scorer;
+
+const char *fk_status_string(fk_status s);
+
+/* Names the build: "fk <version> gfx950". */
+const char *fk_version(void);
+
+/*
+ * Section 3.1 (a generated token joins the cache): for every sequence b and KV head h write
+ * k_new[b][h][:], v_new[b][h][:] and pos_new[b] into slot len[b] of row (b, h), then
+ * len[b] += 1.  k_new, v_new: [batch][n_kv_heads][head_dim] dtype; pos_new: [batch] int32.
+ * A sequence whose len[b] == capacity is left unchanged (nothing is written past the row).
+ */
+fk_status fk_append(const fk_cache_desc *desc, void *K, void *V, int32_t *pos, int32_t *len,
+                    const void *k_new, const void *v_new, const int32_t *pos_new, void *stream);
+
+/* Bytes of device workspace fk_decode_attn needs for rows of up to max_len entries (0 on bad args). */
+size_t fk_decode_attn_workspace(const fk_cache_desc *desc, int32_t max_len);
+
+/*
+ * Appendix A, "Problem Setup" (attention over the retained set, renormalised softmax):
+ *   out[b][hq][:] = sum_{i < len[b]} softmax_i(softmax_scale * <q[b][hq], K[b][hq/g][i]>) V[b][hq/g][i]
+ * q, out: [batch][n_q_heads][head_dim] dtype; accumulation in fp32.  A sequence with
+ * len[b] == 0 gets zeros.  workspace: >= fk_decode_attn_workspace(desc, max_len) bytes,
+ * contents irrelevant on entry, clobbered on exit (FK_ERR_WORKSPACE if too small).
+ */
+fk_status fk_decode_attn(const fk_cache_desc *desc, const void *q, const void *K, const void *V,
+                         const int32_t *len, int32_t max_len, float softmax_scale, void *out,
+                         void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * Section 3.1 Eq. 1 and Appendix B.1 (importance score of every retained pair, features
+ * restricted to the key and value vectors):
+ *   scores[b][h][i] = sum_j gelu(sum_f x_f W1[f][j] + b1[j]) W2[j] + b2,  x = [K[b][h][i], V[b][h][i]]
+ * for i < len[b]; gelu is the exact erf form; fp32 accumulation (bf16: MFMA).  scores:
+ * [batch][n_kv_heads][capacity] fp32; slots >= len[b] are not written.
+ */
+fk_status fk_score_kv(const fk_cache_desc *desc, const void *K, const void *V, const int32_t *len,
+                      int32_t max_len, const fk_scorer *scorer, float *scores, void *stream);
+
+/*
+ * Section 3.1 (keep the most recent L pairs, prune the others to the B - L most important;
+ * deterministic Top-K form).  For every row with len[b] > budget: keep the last
+ * `protect_recent` live slots and, of the other len[b] - protect_recent, the
+ * budget - protect_recent best under the total order (score descending, then slot
+ * ascending = position ascending).  -0 equals +0; NaN ranks below -inf.  The kept slot
+ * indices are written ascending to keep_idx[b][h][0 .. budget-1].  Rows with
+ * len[b] <= budget get keep_idx[j] = j for j < len[b]; the rest of their row is not written.
+ * keep_idx: [batch][n_kv_heads][budget] int32.  pos may be NULL: it is not read, slot order
+ * stands for position order (see the precondition above).
+ * Requires 0 <= protect_recent <= budget <= capacity.
+ */
+fk_status fk_select_keep(const fk_cache_desc *desc, const float *scores, const int32_t *pos,
+                         const int32_t *len, int32_t max_len, int32_t budget,
+                         int32_t protect_recent, int32_t *keep_idx, void *stream);
+
+/*
+ * Section 1 / 3.1 (evicted pairs are discarded for good; stable in-place form): for every row
+ * with len[b] > budget, slot j of K, V and pos receives the former contents of slot
+ * keep_idx[b][h][j], j = 0 .. budget-1 (bit copies; keep_idx ascending with keep_idx[j] >= j,
+ * as fk_select_keep writes it), then len[b] = budget.  Rows with len[b] <= budget are untouched.
+ */
+fk_status fk_compact(const fk_cache_desc *desc, void *K, void *V, int32_t *pos, int32_t *len,
+                     const int32_t *keep_idx, int32_t budget, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FK_H */

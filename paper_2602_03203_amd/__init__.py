@@ -1,0 +1,7 @@
+"""MI355X-native budgeted-KV decode + evict path (ForesightKV generation loop).
+
+`binding` exposes the C ABI of libfk.so (fk_append, fk_decode_attn, fk_score_kv,
+fk_select_keep, fk_compact); `build` compiles it in-tree with hipcc for gfx950.
+"""
+from .binding import (CacheDesc, FkError, fk_append, fk_compact, fk_decode_attn, fk_decode_attn_workspace,  # noqa: F401
+                      fk_score_kv, fk_select_keep, lib, status_string, version)

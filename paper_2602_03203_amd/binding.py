@@ -1,0 +1,142 @@
+"""ctypes binding of libfk.so: same names as the C ABI, argument marshalling only.
+
+Tensors are torch CUDA (ROCm) tensors used as plain device buffers; every step of the
+path runs in the library's HIP kernels.  bf16 buffers may be torch.bfloat16 or raw
+torch.uint16 / torch.int16 bit patterns.  There is no fallback: if the library is not
+built, importing the functions raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from dataclasses import dataclass
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libfk.so")
+
+FK_OK, FK_ERR_INVALID_ARG, FK_ERR_UNSUPPORTED, FK_ERR_WORKSPACE, FK_ERR_LAUNCH = range(5)
+FK_F32, FK_BF16 = 0, 1
+
+SYMBOLS = ["fk_status_string", "fk_version", "fk_append", "fk_decode_attn_workspace", "fk_decode_attn",
+           "fk_score_kv", "fk_select_keep", "fk_compact"]
+
+
+class fk_cache_desc(ctypes.Structure):
+    _fields_ = [("batch", ctypes.c_int32), ("n_q_heads", ctypes.c_int32), ("n_kv_heads", ctypes.c_int32),
+                ("head_dim", ctypes.c_int32), ("capacity", ctypes.c_int32), ("dtype", ctypes.c_int32)]
+
+
+class fk_scorer(ctypes.Structure):
+    _fields_ = [("w1", ctypes.c_void_p), ("b1", ctypes.c_void_p), ("w2", ctypes.c_void_p), ("b2", ctypes.c_void_p),
+                ("hidden", ctypes.c_int32), ("per_head", ctypes.c_int32)]
+
+
+class FkError(RuntimeError):
+    def __init__(self, code: int, where: str):
+        self.code = code
+        super().__init__(f"{where}: {status_string(code)} (fk_status {code})")
+
+
+_lib = None
+
+
+def lib() -> ctypes.CDLL:
+    """Load libfk.so (built in-tree by paper_2602_03203_amd.build); raises if it is missing."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise ImportError(f"{LIB_PATH} is not built: run `python -m paper_2602_03203_amd.build`")
+        L = ctypes.CDLL(LIB_PATH)
+        vp, i32, f32, sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_float, ctypes.c_size_t
+        dp, sp = ctypes.POINTER(fk_cache_desc), ctypes.POINTER(fk_scorer)
+        L.fk_status_string.restype, L.fk_status_string.argtypes = ctypes.c_char_p, [ctypes.c_int]
+        L.fk_version.restype, L.fk_version.argtypes = ctypes.c_char_p, []
+        L.fk_append.restype, L.fk_append.argtypes = ctypes.c_int, [dp, vp, vp, vp, vp, vp, vp, vp, vp]
+        L.fk_decode_attn_workspace.restype, L.fk_decode_attn_workspace.argtypes = sz, [dp, i32]
+        L.fk_decode_attn.restype, L.fk_decode_attn.argtypes = ctypes.c_int, [dp, vp, vp, vp, vp, i32, f32, vp, vp, sz, vp]
+        L.fk_score_kv.restype, L.fk_score_kv.argtypes = ctypes.c_int, [dp, vp, vp, vp, i32, sp, vp, vp]
+        L.fk_select_keep.restype, L.fk_select_keep.argtypes = ctypes.c_int, [dp, vp, vp, vp, i32, i32, i32, vp, vp]
+        L.fk_compact.restype, L.fk_compact.argtypes = ctypes.c_int, [dp, vp, vp, vp, vp, vp, i32, vp]
+        _lib = L
+    return _lib
+
+
+def status_string(code: int) -> str:
+    return lib().fk_status_string(int(code)).decode()
+
+
+def version() -> str:
+    return lib().fk_version().decode()
+
+
+def _check(code: int, where: str) -> None:
+    if code != FK_OK:
+        raise FkError(code, where)
+
+
+def _ptr(t) -> int:
+    if t is None:
+        return 0
+    assert t.is_cuda and t.is_contiguous(), "fk buffers must be contiguous device tensors"
+    return t.data_ptr()
+
+
+def _stream(stream) -> int:
+    s = torch.cuda.current_stream() if stream is None else stream
+    return s.cuda_stream
+
+
+@dataclass
+class CacheDesc:
+    batch: int
+    n_q_heads: int
+    n_kv_heads: int
+    head_dim: int
+    capacity: int
+    dtype: str  # 'f32' | 'bf16'
+
+    def c(self) -> fk_cache_desc:
+        return fk_cache_desc(self.batch, self.n_q_heads, self.n_kv_heads, self.head_dim, self.capacity,
+                             FK_F32 if self.dtype == "f32" else FK_BF16)
+
+    @property
+    def torch_dtype(self):
+        return torch.float32 if self.dtype == "f32" else torch.bfloat16
+
+
+def fk_append(desc: CacheDesc, K, V, pos, length, k_new, v_new, pos_new, stream=None) -> None:
+    _check(lib().fk_append(ctypes.byref(desc.c()), _ptr(K), _ptr(V), _ptr(pos), _ptr(length), _ptr(k_new),
+                           _ptr(v_new), _ptr(pos_new), _stream(stream)), "fk_append")
+
+
+def fk_decode_attn_workspace(desc: CacheDesc, max_len: int) -> int:
+    return int(lib().fk_decode_attn_workspace(ctypes.byref(desc.c()), int(max_len)))
+
+
+def fk_decode_attn(desc: CacheDesc, q, K, V, length, max_len: int, softmax_scale: float, out, workspace,
+                   stream=None) -> None:
+    nbytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(lib().fk_decode_attn(ctypes.byref(desc.c()), _ptr(q), _ptr(K), _ptr(V), _ptr(length), int(max_len),
+                                float(softmax_scale), _ptr(out), _ptr(workspace), nbytes, _stream(stream)),
+           "fk_decode_attn")
+
+
+def fk_score_kv(desc: CacheDesc, K, V, length, max_len: int, W1, b1, W2, b2, scores, stream=None) -> None:
+    """W1 [n_sets, 2D, H] cache dtype; b1, W2 [n_sets, H] fp32; b2 [n_sets] fp32; n_sets in {1, n_kv_heads}."""
+    n_sets, _, hidden = W1.shape
+    sc = fk_scorer(_ptr(W1), _ptr(b1), _ptr(W2), _ptr(b2), int(hidden), 1 if n_sets == desc.n_kv_heads and n_sets > 1 else 0)
+    _check(lib().fk_score_kv(ctypes.byref(desc.c()), _ptr(K), _ptr(V), _ptr(length), int(max_len), ctypes.byref(sc),
+                             _ptr(scores), _stream(stream)), "fk_score_kv")
+
+
+def fk_select_keep(desc: CacheDesc, scores, pos, length, max_len: int, budget: int, protect_recent: int, keep_idx,
+                   stream=None) -> None:
+    _check(lib().fk_select_keep(ctypes.byref(desc.c()), _ptr(scores), _ptr(pos), _ptr(length), int(max_len),
+                                int(budget), int(protect_recent), _ptr(keep_idx), _stream(stream)), "fk_select_keep")
+
+
+def fk_compact(desc: CacheDesc, K, V, pos, length, keep_idx, budget: int, stream=None) -> None:
+    _check(lib().fk_compact(ctypes.byref(desc.c()), _ptr(K), _ptr(V), _ptr(pos), _ptr(length), _ptr(keep_idx),
+                            int(budget), _stream(stream)), "fk_compact")

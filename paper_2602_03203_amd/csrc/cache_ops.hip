@@ -1,0 +1,136 @@
+// fk_append and fk_compact: the two calls that rewrite the cache.
+#include "fk_common.h"
+
+namespace fk {
+
+// ---------------------------------------------------------------------------------------
+// append (Section 3.1: each generated token adds one pair to every KV-head row)
+// one workgroup per sequence; 16-byte chunks of the new K and V rows of all its KV heads
+// ---------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void append_kernel(uint4* __restrict__ K, uint4* __restrict__ V,
+                                                     int32_t* __restrict__ pos, int32_t* __restrict__ len,
+                                                     const uint4* __restrict__ k_new,
+                                                     const uint4* __restrict__ v_new,
+                                                     const int32_t* __restrict__ pos_new, int n_kv,
+                                                     int cap, int chunks /* 16-byte chunks per row */) {
+    const int b = blockIdx.x;
+    const int n = len[b];
+    __syncthreads();  // everyone has read len[b] before it is bumped
+    if (n < 0 || n >= cap) return;
+    const int total = n_kv * chunks;
+    for (int i = threadIdx.x; i < total; i += blockDim.x) {
+        const int h = i / chunks, c = i % chunks;
+        const size_t row = (size_t)b * n_kv + h;
+        const size_t dst = (row * cap + n) * chunks + c;
+        K[dst] = k_new[row * chunks + c];
+        V[dst] = v_new[row * chunks + c];
+    }
+    for (int h = threadIdx.x; h < n_kv; h += blockDim.x) pos[((size_t)b * n_kv + h) * cap + n] = pos_new[b];
+    if (threadIdx.x == 0) len[b] = n + 1;
+}
+
+// ---------------------------------------------------------------------------------------
+// compact (stable in-place gather)
+//
+// keep[] is ascending with keep[j] >= j.  Destination slots are processed in ascending
+// tiles of TILE slots by ONE workgroup per (row, tensor): all sources of a tile are loaded
+// into registers, a barrier, then the tile is stored.  A store of tile t lands in slots
+// [tT, (t+1)T); a source of any later tile is >= (t+1)T, and every source of tile t or of an
+// earlier tile has already been read, so no live source is overwritten.  Entries with
+// keep[j] == j (the untouched prefix) cost no traffic.
+// grid.x = row, grid.y = 0: K, 1: V, 2: pos
+// ---------------------------------------------------------------------------------------
+static constexpr int kCompactThreads = 256;
+static constexpr int kCompactU = 8;
+
+__global__ __launch_bounds__(kCompactThreads) void compact_kernel(uint4* __restrict__ K, uint4* __restrict__ V,
+                                                                  int32_t* __restrict__ pos,
+                                                                  const int32_t* __restrict__ len,
+                                                                  const int32_t* __restrict__ keep, int n_kv,
+                                                                  int cap, int budget, int chunks) {
+    const int row = blockIdx.x;
+    const int b = row / n_kv;
+    const int n = len[b];
+    if (n <= budget) return;
+    const int32_t* kp = keep + (size_t)row * budget;
+    if (blockIdx.y == 2) {
+        int32_t* p = pos + (size_t)row * cap;
+        for (int base = 0; base < budget; base += kCompactThreads * kCompactU) {
+            int32_t val[kCompactU];
+            int src[kCompactU];
+#pragma unroll
+            for (int u = 0; u < kCompactU; ++u) {
+                const int j = base + u * kCompactThreads + threadIdx.x;
+                src[u] = j < budget ? kp[j] : -1;
+                if (src[u] >= 0 && src[u] < n) val[u] = p[src[u]];
+            }
+            __syncthreads();
+#pragma unroll
+            for (int u = 0; u < kCompactU; ++u) {
+                const int j = base + u * kCompactThreads + threadIdx.x;
+                if (src[u] >= 0 && src[u] < n && src[u] != j) p[j] = val[u];
+            }
+        }
+        return;
+    }
+    uint4* X = (blockIdx.y == 0 ? K : V) + (size_t)row * cap * chunks;
+    const int spi = kCompactThreads / chunks;  // slots per load instruction of the workgroup
+    const int sl = threadIdx.x / chunks;       // slot within that group
+    const int c = threadIdx.x % chunks;        // 16-byte chunk of the row
+    for (int base = 0; base < budget; base += spi * kCompactU) {
+        uint4 val[kCompactU];
+        int src[kCompactU];
+#pragma unroll
+        for (int u = 0; u < kCompactU; ++u) {
+            const int j = base + u * spi + sl;
+            src[u] = j < budget ? kp[j] : -1;
+            if (src[u] >= 0 && src[u] < n && src[u] != j) val[u] = X[(size_t)src[u] * chunks + c];
+        }
+        __syncthreads();
+#pragma unroll
+        for (int u = 0; u < kCompactU; ++u) {
+            const int j = base + u * spi + sl;
+            if (src[u] >= 0 && src[u] < n && src[u] != j) X[(size_t)j * chunks + c] = val[u];
+        }
+    }
+}
+
+// after every row has been compacted: len[b] = min(len[b], budget)
+__global__ void clamp_len_kernel(int32_t* __restrict__ len, int batch, int budget) {
+    const int b = blockIdx.x * blockDim.x + threadIdx.x;
+    if (b < batch && len[b] > budget) len[b] = budget;
+}
+
+}  // namespace fk
+
+using namespace fk;
+
+extern "C" fk_status fk_append(const fk_cache_desc* desc, void* K, void* V, int32_t* pos, int32_t* len,
+                               const void* k_new, const void* v_new, const int32_t* pos_new, void* stream) {
+    fk_status s = check_desc(desc);
+    if (s != FK_OK) return s;
+    if (!K || !V || !pos || !len || !k_new || !v_new || !pos_new) return FK_ERR_INVALID_ARG;
+    if (!aligned16(K) || !aligned16(V) || !aligned16(k_new) || !aligned16(v_new)) return FK_ERR_INVALID_ARG;
+    const int chunks = desc->head_dim * (desc->dtype == FK_F32 ? 4 : 2) / 16;
+    hipLaunchKernelGGL(append_kernel, dim3(desc->batch), dim3(256), 0, (hipStream_t)stream, (uint4*)K,
+                       (uint4*)V, pos, len, (const uint4*)k_new, (const uint4*)v_new, pos_new,
+                       desc->n_kv_heads, desc->capacity, chunks);
+    return launch_status();
+}
+
+extern "C" fk_status fk_compact(const fk_cache_desc* desc, void* K, void* V, int32_t* pos, int32_t* len,
+                                const int32_t* keep_idx, int32_t budget, void* stream) {
+    fk_status s = check_desc(desc);
+    if (s != FK_OK) return s;
+    if (!K || !V || !pos || !len || !keep_idx) return FK_ERR_INVALID_ARG;
+    if (budget <= 0 || budget > desc->capacity) return FK_ERR_INVALID_ARG;
+    if (!aligned16(K) || !aligned16(V)) return FK_ERR_INVALID_ARG;
+    const int chunks = desc->head_dim * (desc->dtype == FK_F32 ? 4 : 2) / 16;
+    const int rows = desc->batch * desc->n_kv_heads;
+    hipStream_t st = (hipStream_t)stream;
+    hipLaunchKernelGGL(compact_kernel, dim3(rows, 3), dim3(kCompactThreads), 0, st, (uint4*)K, (uint4*)V,
+                       pos, len, keep_idx, desc->n_kv_heads, desc->capacity, budget, chunks);
+    hipLaunchKernelGGL(clamp_len_kernel, dim3((desc->batch + 255) / 256), dim3(256), 0, st, len,
+                       desc->batch, budget);
+    return launch_status();
+}

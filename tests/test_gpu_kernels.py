@@ -1,0 +1,200 @@
+"""Parity of every C-ABI entry point against the CPU oracle, element by element, on seeded inputs
+that span several tiles and a ragged tail, plus the edge cases each kernel has."""
+import numpy as np
+import pytest
+import torch
+
+import synth_inputs as si
+from util import random_cache, random_q, store
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def gpu():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    import gpu_util
+    import paper_2602_03203_amd as fk
+    fk.lib()                       # the HIP library must be there: no fallback
+    return gpu_util
+
+
+ATTN_SHAPES = [
+    # dtype, D, Hq, Hkv, cap, lens
+    ("f32", 64, 8, 2, 160, [160]),
+    ("bf16", 128, 32, 8, 2176, [2176, 2049]),
+    ("bf16", 128, 8, 2, 700, [700, 513, 1, 0, 64, 65]),
+    ("bf16", 128, 28, 4, 1100, [1100, 777]),          # group of 7
+    ("bf16", 64, 6, 3, 300, [300, 37]),
+    ("f32", 128, 2, 2, 200, [200, 129]),
+    ("f32", 64, 5, 1, 90, [90, 3]),                    # group of 5
+    ("bf16", 128, 8, 1, 260, [260]),                   # group of 8
+]
+
+
+@pytest.mark.parametrize("dtype,D,Hq,Hkv,cap,lens", ATTN_SHAPES)
+def test_decode_attn_matches_oracle(gpu, ora, dtype, D, Hq, Hkv, cap, lens):
+    Bt = len(lens)
+    print(f"attn case {dtype} D={D} Hq={Hq} Hkv={Hkv} cap={cap} lens={lens}", flush=True)
+    c = random_cache(ora, 1000 + D + Hq, dtype, Bt, Hkv, cap, D, lens=lens)
+    q = random_q(2000 + D, dtype, Bt, Hq, D)
+    dev = gpu.DevCache(c, Hq)
+    qd = gpu.to_dev(q)
+    for scale in (D ** -0.5, 0.02, 3.0 * D ** -0.5):      # usual, near-uniform, peaked softmax
+        ref = ora.decode_attn(c, q, scale)
+        got = dev.attn(qd, scale)
+        gpu.assert_attn_close(got, ref, dtype, f"scale {scale}")
+    # a tighter max_len hint that still covers every row gives the same answer
+    got = dev.attn(qd, D ** -0.5, max_len=max(max(lens), 1))
+    gpu.assert_attn_close(got, ora.decode_attn(c, q, D ** -0.5), dtype, "max_len hint")
+
+
+def test_decode_attn_closed_forms_on_device(gpu, ora):
+    """identical keys -> mean of V; one dominant key -> its value."""
+    D, cap = 128, 1000
+    c = random_cache(ora, 77, "bf16", 1, 2, cap, D, lens=[cap])
+    c.K[...] = c.K[:, :, :1]
+    q = random_q(78, "bf16", 1, 8, D)
+    dev = gpu.DevCache(c, 8)
+    got = dev.attn(gpu.to_dev(q), 0.3)
+    mean_v = si.from_bf16_bits(c.V).astype(np.float64).mean(axis=2)
+    for h in range(8):
+        gpu.assert_attn_close(got[0, h], mean_v[0, h // 4], "bf16", "mean of V")
+    c2 = random_cache(ora, 79, "f32", 1, 1, 300, 64, lens=[300], scale=0.01)
+    q2 = random_q(80, "f32", 1, 4, 64)
+    c2.K[0, 0, 217] = 300.0 * q2[0, 2]
+    got2 = gpu.DevCache(c2, 4).attn(gpu.to_dev(q2), 1.0)
+    np.testing.assert_allclose(got2[0, 2], c2.V[0, 0, 217].astype(np.float64), atol=1e-5)
+
+
+SCORE_SHAPES = [
+    ("f32", 64, 64, 2, 160, [160, 33], True),
+    ("bf16", 128, 256, 8, 2176, [2176], True),
+    ("bf16", 128, 256, 2, 600, [600, 257, 1, 0], True),
+    ("bf16", 128, 32, 2, 100, [100, 64], False),       # shared weights, narrow hidden
+    ("bf16", 64, 96, 3, 130, [130, 65], True),
+    ("f32", 128, 20, 1, 70, [70], True),
+]
+
+
+@pytest.mark.parametrize("dtype,D,H,Hkv,cap,lens,per_head", SCORE_SHAPES)
+def test_score_kv_matches_oracle(gpu, ora, dtype, D, H, Hkv, cap, lens, per_head):
+    import paper_2602_03203_amd as fk
+    Bt = len(lens)
+    print(f"score case {dtype} D={D} H={H} Hkv={Hkv} cap={cap} lens={lens}", flush=True)
+    c = random_cache(ora, 3000 + H, dtype, Bt, Hkv, cap, D, lens=lens, scale=0.5)
+    nset = Hkv if per_head else 1
+    F = 2 * D
+    W1 = store((si.normal(5, si.T_W1, 0, np.arange(nset * F * H)).reshape(nset, F, H) / np.sqrt(F)).astype(np.float32), dtype)
+    b1 = (si.normal(5, si.T_B1, 0, np.arange(nset * H)).reshape(nset, H) * 0.2).astype(np.float32)
+    W2 = (si.normal(5, si.T_W2, 0, np.arange(nset * H)).reshape(nset, H) / np.sqrt(H)).astype(np.float32)
+    b2 = (si.normal(5, si.T_B2, 0, np.arange(nset)) * 0.3).astype(np.float32)
+    ref = ora.score_kv(c, W1, b1, W2, b2)
+    dev = gpu.DevCache(c, Hkv)
+    fk.fk_score_kv(dev.desc, dev.K, dev.V, dev.len, cap, gpu.to_dev(W1), gpu.to_dev(b1), gpu.to_dev(W2), gpu.to_dev(b2), dev.scores)
+    got = dev.scores.cpu().numpy()
+    gpu.assert_scores_close(got, ref, lens, "scores")
+    for b in range(Bt):                                   # slots past len are not written
+        assert np.isnan(got[b, :, lens[b]:]).all()
+
+
+SELECT_CASES = [
+    # Bt, Hkv, cap, lens, budget, recent, ties
+    (1, 2, 160, [160], 128, 32, 0),
+    (16, 8, 2176, [2176] * 16, 2048, 128, 0),
+    (2, 4, 2176, [2176, 2100], 2048, 128, 6),          # heavy ties
+    (3, 2, 5000, [5000, 3001, 2999], 3000, 64, 3),     # far over budget, exactly at budget + 1, under budget
+    (2, 1, 300, [300, 300], 200, 0, 2),                # nothing protected
+    (2, 1, 300, [300, 300], 200, 200, 0),              # everything kept is protected
+    (1, 3, 1500, [1500], 1, 0, 2),                     # budget 1
+    (2, 2, 40000, [40000, 33000], 8192, 128, 0),       # long rows (ragged-batch first event)
+]
+
+
+@pytest.mark.parametrize("Bt,Hkv,cap,lens,budget,recent,ties", SELECT_CASES)
+def test_select_keep_bit_exact(gpu, ora, Bt, Hkv, cap, lens, budget, recent, ties):
+    import paper_2602_03203_amd as fk
+    print(f"select case Bt={Bt} Hkv={Hkv} cap={cap} lens={lens} B={budget} R={recent} ties={ties}", flush=True)
+    sc = si.gen_scores(4000 + cap + ties, (Bt, Hkv, cap), ties=ties)
+    pos = np.tile(np.arange(cap, dtype=np.int32) * 2 + 3, (Bt, Hkv, 1))
+    ln = np.asarray(lens, np.int32)
+    ref = ora.select_keep(sc, pos, ln, budget, recent, "sort")
+    desc = fk.CacheDesc(Bt, Hkv, Hkv, 128, cap, "bf16")
+    keep = torch.full((Bt, Hkv, budget), -1, dtype=torch.int32, device="cuda")
+    fk.fk_select_keep(desc, gpu.to_dev(sc), gpu.to_dev(pos), gpu.to_dev(ln), cap, budget, recent, keep)
+    assert np.array_equal(keep.cpu().numpy(), ref)
+
+
+def test_select_keep_special_values(gpu, ora):
+    import paper_2602_03203_amd as fk
+    cap, budget, recent = 1200, 700, 100
+    sc = si.gen_scores(4242, (1, 4, cap), ties=4)
+    flat = sc.reshape(-1)
+    special = np.array([np.nan, -np.nan, np.inf, -np.inf, 0.0, -0.0, 1e-45, -1e-45, 3.4e38, -3.4e38], np.float32)
+    idx = (si.hash_u64(1, si.T_FLAG, 0, np.arange(1500)) % np.uint64(flat.size)).astype(np.int64)
+    flat[idx] = special[np.arange(1500) % len(special)]
+    sc[0, 3] = 0.0
+    sc[0, 3, ::2] = -0.0                                   # a row of +0 / -0 only: pure position tie-break
+    pos = np.arange(cap, dtype=np.int32)[None, None].repeat(4, 1)
+    ln = np.array([cap], np.int32)
+    ref = ora.select_keep(sc, pos, ln, budget, recent, "rank")
+    desc = fk.CacheDesc(1, 4, 4, 128, cap, "bf16")
+    keep = torch.full((1, 4, budget), -1, dtype=torch.int32, device="cuda")
+    fk.fk_select_keep(desc, gpu.to_dev(sc), None, gpu.to_dev(ln), cap, budget, recent, keep)
+    assert np.array_equal(keep.cpu().numpy(), ref)
+    assert keep[0, 3].cpu().tolist() == list(range(600)) + list(range(1100, 1200))
+
+
+COMPACT_CASES = [("f32", 64, 1, 2, 160, [160], 128), ("bf16", 128, 3, 2, 2176, [2176, 2050, 2048], 2048),
+                 ("bf16", 64, 2, 3, 333, [333, 100], 150), ("f32", 128, 1, 1, 700, [700], 300)]
+
+
+@pytest.mark.parametrize("dtype,D,Bt,Hkv,cap,lens,budget", COMPACT_CASES)
+def test_compact_bit_exact(gpu, ora, dtype, D, Bt, Hkv, cap, lens, budget):
+    import paper_2602_03203_amd as fk
+    print(f"compact case {dtype} D={D} Bt={Bt} Hkv={Hkv} cap={cap} lens={lens} B={budget}", flush=True)
+    c = random_cache(ora, 5000 + cap, dtype, Bt, Hkv, cap, D, lens=lens)
+    recent = min(32, budget)
+    sc = si.gen_scores(5001 + cap, (Bt, Hkv, cap), ties=5)
+    keep = ora.select_keep(sc, c.pos, c.len, budget, recent)
+    patterns = [keep]
+    # adversarial overlaps on the first row: evict the head block / every other / a middle block
+    n0 = lens[0]
+    if n0 > budget:
+        for pat in (np.arange(n0 - budget, n0), np.sort(np.r_[np.arange(0, 2 * (n0 - budget), 2), np.arange(2 * (n0 - budget), n0)])[:budget],
+                    np.r_[np.arange(7), np.arange(7 + n0 - budget, n0)]):
+            k2 = keep.copy()
+            k2[0, :] = pat.astype(np.int32)
+            patterns.append(k2)
+    for kp in patterns:
+        host = c.copy()
+        dev = gpu.DevCache(c, Hkv)
+        ora.compact(host, kp, budget)
+        fk.fk_compact(dev.desc, dev.K, dev.V, dev.pos, dev.len, gpu.to_dev(kp), budget)
+        got = dev.host(ora)
+        assert np.array_equal(got.len, host.len)
+        assert np.array_equal(got.pos, host.pos)
+        assert np.array_equal(got.K, host.K) and np.array_equal(got.V, host.V)
+
+
+@pytest.mark.parametrize("dtype,D", [("f32", 64), ("bf16", 128), ("bf16", 64), ("f32", 128)])
+def test_append_bit_exact(gpu, ora, dtype, D):
+    import paper_2602_03203_amd as fk
+    Bt, Hkv, cap = 5, 3, 40
+    lens = [0, 39, 40, 17, 5]                           # one sequence is full: must be left alone
+    c = random_cache(ora, 6000 + D, dtype, Bt, Hkv, cap, D, lens=lens)
+    dev = gpu.DevCache(c, Hkv)
+    k_new = random_q(6001, dtype, Bt, Hkv, D)
+    v_new = random_q(6002, dtype, Bt, Hkv, D)
+    pos_new = np.array([0, 500, 501, 502, 503], np.int32)
+    fk.fk_append(dev.desc, dev.K, dev.V, dev.pos, dev.len, gpu.to_dev(k_new), gpu.to_dev(v_new), gpu.to_dev(pos_new))
+    got = dev.host(ora)
+    host = c.copy()
+    for b in range(Bt):                                   # oracle append refuses the full row as a whole; do rows one by one
+        if lens[b] < cap:
+            sub = ora.Cache(dtype, host.K[b:b + 1].copy(), host.V[b:b + 1].copy(), host.pos[b:b + 1].copy(), host.len[b:b + 1].copy())
+            ora.append(sub, k_new[b:b + 1], v_new[b:b + 1], pos_new[b:b + 1])
+            host.K[b], host.V[b], host.pos[b], host.len[b] = sub.K[0], sub.V[0], sub.pos[0], sub.len[0]
+    assert np.array_equal(got.len, host.len) and np.array_equal(got.pos, host.pos)
+    assert np.array_equal(got.K, host.K) and np.array_equal(got.V, host.V)

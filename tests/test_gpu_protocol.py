@@ -1,0 +1,130 @@
+"""Lock-step parity of the whole path (append, attention, score, select, compact) against the
+oracle over real step / event sequences.
+
+At every step the attention outputs are compared; at every event the device scores are compared
+with the oracle's, then BOTH sides select on the oracle's fp32 scores (keep-sets bit exact), and
+after compaction K, V, pos and len are compared bit for bit.  The device's own scores also go
+through device selection and must equal the oracle's selection on those same fp32 values.
+"""
+import numpy as np
+import pytest
+import torch
+
+import synth_inputs as si
+from util import bulk_step_inputs, scorer_storage, workload_cache
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def gpu():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    import gpu_util
+    import paper_2602_03203_amd as fk
+    fk.lib()
+    return gpu_util
+
+
+def lockstep(gpu, ora, w, n_steps, sample_rows=None, scale=None, check_every=1):
+    """Run the device on the whole workload and the oracle on `sample_rows` [(b, h), ...]
+    (None = every row).  Returns the number of events checked."""
+    import paper_2602_03203_amd as fk
+    scale = w.softmax_scale if scale is None else scale
+    lens0 = si.initial_lengths(w)
+    B, L, g = w.budget, w.interval, w.group
+    print(f"lockstep {w.name}: building prompt cache", flush=True)
+    full = workload_cache(ora, w)
+    dev = gpu.DevCache(full, w.n_q_heads)
+    W1, b1, W2, b2 = scorer_storage(w)
+    dW = [gpu.to_dev(x) for x in (W1, b1, W2, b2)]
+    rows = [(b, h) for b in range(w.batch) for h in range(w.n_kv_heads)] if sample_rows is None else sample_rows
+    # one single-row oracle cache per sampled row (rows are independent)
+    subs = {}
+    for (b, h) in rows:
+        subs[(b, h)] = ora.Cache(w.dtype, full.K[b:b + 1, h:h + 1].copy(), full.V[b:b + 1, h:h + 1].copy(),
+                                 full.pos[b:b + 1, h:h + 1].copy(), full.len[b:b + 1].copy())
+    del full
+    q_all, k_all, v_all, p_all = bulk_step_inputs(w, 0, 0, n_steps, lens0)
+    dq, dk, dv, dp = (gpu.to_dev(x) for x in (q_all, k_all, v_all, p_all))
+    keep_dev = torch.full((w.batch, w.n_kv_heads, B), -1, dtype=torch.int32, device="cuda")
+    keep_own = torch.full_like(keep_dev, -1)
+    events = 0
+    max_len = int(lens0.max())
+    for t in range(n_steps):
+        fk.fk_append(dev.desc, dev.K, dev.V, dev.pos, dev.len, dk[t], dv[t], dp[t])
+        max_len += 1
+        fk.fk_decode_attn(dev.desc, dq[t], dev.K, dev.V, dev.len, min(max_len, w.capacity), scale, dev.out, dev.ws)
+        for (b, h), c in subs.items():
+            ora.append(c, k_all[t, b:b + 1, h:h + 1], v_all[t, b:b + 1, h:h + 1], p_all[t, b:b + 1])
+        if t % check_every == 0 or (t + 1) % L == 0:
+            got = gpu.out_to_f64(dev.out)
+            for (b, h), c in subs.items():
+                ref = ora.decode_attn(c, q_all[t, b:b + 1, h * g:(h + 1) * g], scale)
+                gpu.assert_attn_close(got[b, h * g:(h + 1) * g], ref[0], w.dtype, f"step {t} row ({b},{h})")
+        if (t + 1) % L == 0:
+            print(f"  event after step {t}, max_len {max_len}", flush=True)
+            fk.fk_score_kv(dev.desc, dev.K, dev.V, dev.len, min(max_len, w.capacity), *dW, dev.scores)
+            own = dev.scores.clone()
+            fk.fk_select_keep(dev.desc, own, dev.pos, dev.len, min(max_len, w.capacity), B, L, keep_own)
+            own_h, keep_own_h = own.cpu().numpy(), keep_own.cpu().numpy()
+            inject = own_h.copy()
+            refs = {}
+            for (b, h), c in subs.items():
+                n = int(c.len[0])
+                sc = ora.score_kv(c, W1[h:h + 1], b1[h:h + 1], W2[h:h + 1], b2[h:h + 1])
+                gpu.assert_scores_close(own_h[b:b + 1, h:h + 1], sc, [n], f"event at step {t}")
+                sc32 = sc.astype(np.float32)
+                refs[(b, h)] = (sc32, n)
+                inject[b, h, :n] = sc32[0, 0, :n]
+                # the device's own fp32 scores, selected by the oracle, equal the device's selection
+                k_own = ora.select_keep(np.ascontiguousarray(own_h[b:b + 1, h:h + 1]), c.pos, c.len, B, L, "sort")
+                if n > B:
+                    assert np.array_equal(keep_own_h[b, h], k_own[0, 0]), f"own-score keep-set differs, row ({b},{h})"
+            # both sides select on the oracle's scores
+            dev.scores.copy_(torch.from_numpy(inject).cuda())
+            fk.fk_select_keep(dev.desc, dev.scores, dev.pos, dev.len, min(max_len, w.capacity), B, L, keep_dev)
+            keep_h = keep_dev.cpu().numpy()
+            fk.fk_compact(dev.desc, dev.K, dev.V, dev.pos, dev.len, keep_dev, B)
+            host = dev.host(ora)
+            for (b, h), c in subs.items():
+                sc32, n = refs[(b, h)]
+                keep_ref = ora.select_keep(sc32, c.pos, c.len, B, L, "sort")
+                if n > B:
+                    assert np.array_equal(keep_h[b, h], keep_ref[0, 0]), f"keep-set differs at step {t}, row ({b},{h})"
+                ora.compact(c, keep_ref, B)
+                m = int(c.len[0])
+                assert host.len[b] == m
+                assert np.array_equal(host.pos[b, h, :m], c.pos[0, 0, :m])
+                assert np.array_equal(host.K[b, h, :m], c.K[0, 0, :m]) and np.array_equal(host.V[b, h, :m], c.V[0, 0, :m])
+            max_len = min(max_len, B) if max_len > B else max_len
+            events += 1
+    return events
+
+
+def test_tiny_workload_full_run(gpu, ora):
+    """configs[0] end to end: 512 steps, 16 event clocks (14 with rows over budget), every row."""
+    w = si.config(0)
+    assert lockstep(gpu, ora, w, w.steps) == 16
+
+
+def test_tiny_workload_peaked_softmax(gpu, ora):
+    w = si.config(0)
+    lockstep(gpu, ora, w, 200, scale=1.0)
+
+
+def test_qwen3_4b_layer_shape_sampled_rows(gpu, ora):
+    """configs[1] shapes and launch configuration (batch 16, 32/8 heads, D 128, bf16, B 2048, L 128,
+    capacity 2176); the prompt is lengthened so that two events fall inside 400 steps.  The device
+    runs all 128 rows; the oracle follows 4 sampled rows."""
+    w = si.config(1).scaled(prompt=1920)
+    rows = [(0, 0), (5, 3), (11, 6), (15, 7)]
+    for scale in (w.softmax_scale, 128.0 ** 0.5):       # near-uniform and unit-variance logits
+        assert lockstep(gpu, ora, w, 400 if scale == w.softmax_scale else 260, sample_rows=rows, scale=scale, check_every=16) >= 2
+
+
+def test_gqa7_mixture_sampled_rows(gpu, ora):
+    """configs[3] shapes (28/4 heads, D 128, B 4096, L 64) with duplicate-heavy keys: exact score ties."""
+    w = si.config(3).scaled(layers=1, batch=4, prompt=4096 - 64)
+    rows = [(0, 0), (3, 2)]
+    assert lockstep(gpu, ora, w, 200, sample_rows=rows, scale=128.0 ** 0.5, check_every=16) >= 2

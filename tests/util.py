@@ -88,3 +88,27 @@ def scorer_storage(w: si.Workload, layer=0, head_sel=None):
         hs = np.asarray(head_sel)
         W1, b1, W2, b2 = W1[hs], b1[hs], W2[hs], b2[hs]
     return si.storage_array(W1, w.dtype), b1, W2, b2
+
+
+def bulk_step_inputs(w: si.Workload, layer, t0, t1, lens0, batch_sel=None, kv_head_sel=None):
+    """Inputs of decode steps t0 .. t1-1 at once, storage form:
+    q [steps, nb, nhq, D], k_new, v_new [steps, nb, nhk, D], pos_new [steps, nb]."""
+    bs = np.arange(w.batch) if batch_sel is None else np.asarray(batch_sel)
+    hk = np.arange(w.n_kv_heads) if kv_head_sel is None else np.asarray(kv_head_sel)
+    g = w.group
+    hq = (hk[:, None] * g + np.arange(g)[None, :]).reshape(-1)
+    steps, D = t1 - t0, w.head_dim
+    st = np.float32 if w.dtype == "f32" else np.uint16
+    q = np.empty((steps, len(bs), len(hq), D), st)
+    k = np.empty((steps, len(bs), len(hk), D), st)
+    v = np.empty((steps, len(bs), len(hk), D), st)
+    pos = np.empty((steps, len(bs)), np.int32)
+    for i, b in enumerate(bs):
+        p0 = int(lens0[b]) + t0
+        pos[:, i] = np.arange(p0, p0 + steps)
+        qq = si.gen_q(w, layer, p0, p0 + steps, batch_sel=[b], head_sel=hq)[0]          # [nhq, steps, D]
+        kk, vv = si.gen_kv(w, layer, p0, p0 + steps, batch_sel=[b], head_sel=hk)
+        q[:, i] = si.storage_array(qq.transpose(1, 0, 2), w.dtype)
+        k[:, i] = si.storage_array(kk[0].transpose(1, 0, 2), w.dtype)
+        v[:, i] = si.storage_array(vv[0].transpose(1, 0, 2), w.dtype)
+    return q, k, v, pos
