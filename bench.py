@@ -1,0 +1,247 @@
+#!/usr/bin/env python3
+"""Benchmark of the budgeted-KV decode + evict path on one MI355X.
+
+A "step" is one pass of the whole hot path over one batch: append the new pair, attend over the
+retained cache, and after every L-th step run the eviction event (score, select, compact).
+Default workload: the Qwen3-4B single-layer shape (batch 16, 32 query / 8 KV heads, head_dim 128,
+bf16 K/V, prompt 512, budget 2048, eviction every 128 steps, 8192 decode steps).  All inputs are
+seeded synthetic data, resident in HBM before the timed region starts.
+
+Prints ONE JSON line: decode tokens/s for the whole run, the roofline record of the dominant kernel
+(decode attention; algorithmic bytes / HIP-event time of its launches) and the CPU oracle timed on a
+bounded sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+from concurrent.futures import ThreadPoolExecutor
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+import synth_inputs as si  # noqa: E402
+
+HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def gen_step_inputs(w: si.Workload, lens0: np.ndarray, n_steps: int, threads: int):
+    """q [T,Bt,Hq,D], k_new, v_new [T,Bt,Hkv,D] storage arrays and pos_new [T,Bt] for steps 0..T-1."""
+    D, Bt = w.head_dim, w.batch
+    st = np.float32 if w.dtype == "f32" else np.uint16
+    q = np.empty((n_steps, Bt, w.n_q_heads, D), st)
+    k = np.empty((n_steps, Bt, w.n_kv_heads, D), st)
+    v = np.empty((n_steps, Bt, w.n_kv_heads, D), st)
+    pos = np.empty((n_steps, Bt), np.int32)
+    chunk = 256
+    jobs = [(b, t0, min(t0 + chunk, n_steps)) for b in range(Bt) for t0 in range(0, n_steps, chunk)]
+
+    def work(job):
+        b, t0, t1 = job
+        p0 = int(lens0[b]) + t0
+        pos[t0:t1, b] = np.arange(p0, p0 + (t1 - t0))
+        qq = si.gen_q(w, 0, p0, p0 + (t1 - t0), batch_sel=[b])[0]
+        kk, vv = si.gen_kv(w, 0, p0, p0 + (t1 - t0), batch_sel=[b])
+        q[t0:t1, b] = si.storage_array(qq.transpose(1, 0, 2), w.dtype)
+        k[t0:t1, b] = si.storage_array(kk[0].transpose(1, 0, 2), w.dtype)
+        v[t0:t1, b] = si.storage_array(vv[0].transpose(1, 0, 2), w.dtype)
+
+    with ThreadPoolExecutor(max_workers=threads) as ex:
+        list(ex.map(work, jobs))
+    return q, k, v, pos
+
+
+def gen_prompt(w: si.Workload, lens0: np.ndarray, threads: int):
+    """Prompt cache as storage arrays K, V [Bt,Hkv,cap,D], pos [Bt,Hkv,cap]."""
+    st = np.float32 if w.dtype == "f32" else np.uint16
+    K = np.zeros((w.batch, w.n_kv_heads, w.capacity, w.head_dim), st)
+    V = np.zeros_like(K)
+    pos = np.full((w.batch, w.n_kv_heads, w.capacity), -1, np.int32)
+
+    def work(b):
+        n = int(lens0[b])
+        kk, vv = si.gen_kv(w, 0, 0, n, batch_sel=[b])
+        K[b, :, :n] = si.storage_array(kk[0], w.dtype)
+        V[b, :, :n] = si.storage_array(vv[0], w.dtype)
+        pos[b, :, :n] = np.arange(n, dtype=np.int32)
+
+    with ThreadPoolExecutor(max_workers=threads) as ex:
+        list(ex.map(work, range(w.batch)))
+    return K, V, pos
+
+
+def len_schedule(w: si.Workload, lens0: np.ndarray, n_steps: int):
+    """Host replay of the protocol's cache sizes: lens_at_attn [T, Bt] (after the append of step t)."""
+    lens = lens0.astype(np.int64).copy()
+    out = np.empty((n_steps, w.batch), np.int64)
+    ev = []
+    for t in range(n_steps):
+        lens += 1
+        out[t] = lens
+        if (t + 1) % w.interval == 0:
+            ev.append(lens.copy())
+            lens = np.minimum(lens, w.budget)
+    return out, ev
+
+
+def attn_bytes(w: si.Workload, lens_row: np.ndarray) -> float:
+    """Algorithmic bytes of one attention launch: K and V once per KV head, plus q and out."""
+    e = w.elem_bytes
+    return float(w.n_kv_heads * lens_row.sum() * w.head_dim * 2 * e + w.batch * w.n_q_heads * w.head_dim * 2 * e)
+
+
+def cpu_baseline(w: si.Workload, threads: int, windows: int = 3):
+    """Time the CPU oracle, as it stands, on a bounded sample of the same workload: the full batch at
+    steady state (cache at budget) for `windows` eviction windows, each L decode steps (append +
+    attention) and one eviction event (score + select + compact)."""
+    import oracle
+    oracle.set_threads(threads)
+    B, L, Bt = w.budget, w.interval, w.batch
+    wl = w.scaled(prompt=B)  # steady state: rows already hold B pairs
+    c = oracle.new_cache(w.dtype, Bt, w.n_kv_heads, w.capacity, w.head_dim)
+    K, V = si.gen_kv(wl, 0, 0, B)
+    c.K[:, :, :B], c.V[:, :, :B] = si.storage_array(K, w.dtype), si.storage_array(V, w.dtype)
+    c.pos[:, :, :B] = np.arange(B, dtype=np.int32)
+    c.len[:] = B
+    W1, b1, W2, b2 = si.gen_scorer(w, 0)
+    scorer = (si.storage_array(W1, w.dtype), b1, W2, b2)
+    n_steps = windows * L
+    qs = si.storage_array(si.gen_q(wl, 0, B, B + n_steps), w.dtype)
+    ks, vs = (si.storage_array(x, w.dtype) for x in si.gen_kv(wl, 0, B, B + n_steps))
+    step_in = [(np.ascontiguousarray(qs[:, :, t]), np.ascontiguousarray(ks[:, :, t]), np.ascontiguousarray(vs[:, :, t]),
+                np.full(Bt, B + t, np.int32)) for t in range(n_steps)]
+    t0 = time.perf_counter()
+    oracle.run_protocol(c, lambda t: step_in[t], n_steps, scorer, B, L, w.softmax_scale, method="sort")
+    dt = time.perf_counter() - t0
+    assert int(c.len[0]) == B
+    return {"value": Bt * n_steps / dt, "unit": "tokens/s", "cores": threads, "kind": "oracle",
+            "sample": f"full batch ({Bt} sequences x {w.n_kv_heads} KV heads) at steady state (cache {B}..{B + L}): "
+                      f"{windows} windows of {L} decode steps + 1 eviction event each = {n_steps} steps, {dt:.1f}s CPU"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=None, help="timed decode steps (default: the workload's)")
+    ap.add_argument("--warmup", type=int, default=256)
+    ap.add_argument("--config", type=int, default=1)
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
+    ap.add_argument("--no-kernel-timing", action="store_true", help="skip the HIP-event pass over the attention launches")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on ONE GPU (rows are independent; see DESIGN.md for how it would shard); use --gpus 1")
+
+    import torch
+    import paper_2602_03203_amd as fk
+    fk.lib()  # fail loudly if the HIP library is missing
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    host_threads = min(16, os.cpu_count() or 1)
+
+    w = si.config(args.config)
+    if w.layers != 1:
+        sys.exit("bench.py times single-layer workloads (configs 0, 1, 4)")
+    K_steps = args.steps if args.steps is not None else w.steps
+    W_steps = args.warmup
+    n_gen = max(K_steps, W_steps)
+    lens0 = si.initial_lengths(w)
+    B, L = w.budget, w.interval
+
+    t0 = time.time()
+    Kh, Vh, posh = gen_prompt(w, lens0, host_threads)
+    qh, kh, vh, ph = gen_step_inputs(w, lens0, n_gen, host_threads)
+    log(f"[bench] generated {w.name}: prompt + {n_gen} steps in {time.time() - t0:.1f}s")
+
+    def dev(a):
+        if a.dtype == np.uint16:
+            return torch.from_numpy(a.view(np.int16)).cuda().view(torch.bfloat16)
+        return torch.from_numpy(a).cuda()
+
+    K0, V0, pos0, len0 = dev(Kh), dev(Vh), dev(posh), dev(lens0.astype(np.int32))
+    dq, dk, dv, dp = dev(qh), dev(kh), dev(vh), dev(ph)
+    del Kh, Vh, qh, kh, vh
+    W1, b1, W2, b2 = si.gen_scorer(w, 0)
+    dW = [dev(si.storage_array(W1, w.dtype)), dev(b1), dev(W2), dev(b2)]
+    desc = fk.CacheDesc(w.batch, w.n_q_heads, w.n_kv_heads, w.head_dim, w.capacity, w.dtype)
+    Kc, Vc, posc, lenc = (torch.empty_like(x) for x in (K0, V0, pos0, len0))
+    ws = fk.new_attn_workspace(desc)
+    out = torch.empty((w.batch, w.n_q_heads, w.head_dim), dtype=desc.torch_dtype, device="cuda")
+    scores = torch.zeros((w.batch, w.n_kv_heads, w.capacity), dtype=torch.float32, device="cuda")
+    keep = torch.zeros((w.batch, w.n_kv_heads, B), dtype=torch.int32, device="cuda")
+    lens_at, _ = len_schedule(w, lens0, n_gen)
+    max_at = lens_at.max(axis=1)
+    scale = w.softmax_scale
+    stream = torch.cuda.current_stream()
+
+    def reset():
+        Kc.copy_(K0); Vc.copy_(V0); posc.copy_(pos0); lenc.copy_(len0)
+
+    def run(n_steps, ev_pairs=None):
+        for t in range(n_steps):
+            ml = int(min(max_at[t], w.capacity))
+            if ev_pairs is not None:
+                ev_pairs[t][0].record(stream)
+            fk.fk_decode_step(desc, dq[t], Kc, Vc, posc, lenc, dk[t], dv[t], dp[t], ml, scale, out, ws, stream)
+            if ev_pairs is not None:
+                ev_pairs[t][1].record(stream)
+            if (t + 1) % L == 0:
+                fk.fk_score_kv(desc, Kc, Vc, lenc, ml, *dW, scores, stream)
+                fk.fk_select_keep(desc, scores, posc, lenc, ml, B, L, keep, stream)
+                fk.fk_compact(desc, Kc, Vc, posc, lenc, keep, B, stream)
+
+    # warm-up (untimed), then restart from the prompt
+    reset()
+    run(W_steps)
+    torch.cuda.synchronize()
+    reset()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    run(K_steps)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    final_len = lenc.cpu().numpy()
+    expect_len = len_schedule(w, lens0, K_steps)[0][-1]
+    expect_len = np.where((K_steps % L == 0) & (expect_len > B), B, expect_len)
+    assert np.array_equal(final_len, expect_len), (final_len, expect_len)
+
+    tokens_per_s = w.batch * K_steps / wall
+    total_attn_bytes = sum(attn_bytes(w, lens_at[t]) for t in range(K_steps))
+    result = {
+        "metric": "decode tokens/s, budgeted KV decode+evict (attention + scorer + top-k + compaction), one layer",
+        "value": tokens_per_s, "unit": "tokens/s", "n_gpus": 1, "steps": K_steps, "warmup": W_steps,
+        "ms_per_step": 1e3 * wall / K_steps, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": w.dtype, "data": "synthetic",
+        "config": {"workload": w.name, "batch": w.batch, "n_q_heads": w.n_q_heads, "n_kv_heads": w.n_kv_heads,
+                   "head_dim": w.head_dim, "prompt": w.prompt, "budget": B, "eviction_interval": L,
+                   "capacity": w.capacity, "scorer_hidden": w.hidden},
+        "path_gbs_algorithmic": total_attn_bytes / wall / 1e9,
+    }
+
+    if not args.no_kernel_timing:
+        # second pass over the same steps with HIP events around every attention launch (same stream)
+        reset()
+        pairs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(K_steps)]
+        run(K_steps, pairs)
+        torch.cuda.synchronize()
+        ms = np.array([a.elapsed_time(b) for a, b in pairs])
+        avg_bytes = total_attn_bytes / K_steps
+        achieved = avg_bytes / (ms.mean() * 1e-3) / 1e9
+        result["roofline"] = {"kernel": "attn_kernel (fk_decode_step: append + split-K attention + merge, one launch)", "bound": "hbm", "achieved": achieved,
+                              "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                              "avg_launch_us": float(ms.mean() * 1e3), "algorithmic_bytes_per_launch": avg_bytes}
+    if not args.no_cpu:
+        result["cpu_baseline"] = cpu_baseline(w, host_threads)
+    print(json.dumps(result), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -81,19 +81,34 @@ const char *fk_version(void);
 fk_status fk_append(const fk_cache_desc *desc, void *K, void *V, int32_t *pos, int32_t *len,
                     const void *k_new, const void *v_new, const int32_t *pos_new, void *stream);
 
-/* Bytes of device workspace fk_decode_attn needs for rows of up to max_len entries (0 on bad args). */
+/*
+ * Bytes of device workspace fk_decode_attn / fk_decode_step need (0 on bad args).  The size does
+ * not depend on max_len, so one workspace serves every call on this descriptor.  The workspace
+ * starts with arrival counters: the caller zero-fills it ONCE after allocating it; every call
+ * leaves the counters at zero again.  Calls sharing a workspace must not overlap in time.
+ */
 size_t fk_decode_attn_workspace(const fk_cache_desc *desc, int32_t max_len);
 
 /*
  * Appendix A, "Problem Setup" (attention over the retained set, renormalised softmax):
  *   out[b][hq][:] = sum_{i < len[b]} softmax_i(softmax_scale * <q[b][hq], K[b][hq/g][i]>) V[b][hq/g][i]
  * q, out: [batch][n_q_heads][head_dim] dtype; accumulation in fp32.  A sequence with
- * len[b] == 0 gets zeros.  workspace: >= fk_decode_attn_workspace(desc, max_len) bytes,
- * contents irrelevant on entry, clobbered on exit (FK_ERR_WORKSPACE if too small).
+ * len[b] == 0 gets zeros.  workspace: >= fk_decode_attn_workspace(desc, max_len) bytes, zero-filled
+ * once by the caller (see above); FK_ERR_WORKSPACE if missing or too small.  One launch.
  */
 fk_status fk_decode_attn(const fk_cache_desc *desc, const void *q, const void *K, const void *V,
                          const int32_t *len, int32_t max_len, float softmax_scale, void *out,
                          void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * One decode step in ONE launch: fk_append followed by fk_decode_attn (Section 3.1 for the append,
+ * Appendix A "Problem Setup" for the attention), with the same arguments and results as the two
+ * calls in that order; the new pair takes part in the attention.  max_len bounds len[b] + 1.
+ */
+fk_status fk_decode_step(const fk_cache_desc *desc, const void *q, void *K, void *V, int32_t *pos,
+                         int32_t *len, const void *k_new, const void *v_new, const int32_t *pos_new,
+                         int32_t max_len, float softmax_scale, void *out, void *workspace,
+                         size_t workspace_bytes, void *stream);
 
 /*
  * Section 3.1 Eq. 1 and Appendix B.1 (importance score of every retained pair, features

@@ -19,7 +19,7 @@ LIB_PATH = os.path.join(_HERE, "libfk.so")
 FK_OK, FK_ERR_INVALID_ARG, FK_ERR_UNSUPPORTED, FK_ERR_WORKSPACE, FK_ERR_LAUNCH = range(5)
 FK_F32, FK_BF16 = 0, 1
 
-SYMBOLS = ["fk_status_string", "fk_version", "fk_append", "fk_decode_attn_workspace", "fk_decode_attn",
+SYMBOLS = ["fk_status_string", "fk_version", "fk_append", "fk_decode_attn_workspace", "fk_decode_attn", "fk_decode_step",
            "fk_score_kv", "fk_select_keep", "fk_compact"]
 
 
@@ -56,6 +56,7 @@ def lib() -> ctypes.CDLL:
         L.fk_append.restype, L.fk_append.argtypes = ctypes.c_int, [dp, vp, vp, vp, vp, vp, vp, vp, vp]
         L.fk_decode_attn_workspace.restype, L.fk_decode_attn_workspace.argtypes = sz, [dp, i32]
         L.fk_decode_attn.restype, L.fk_decode_attn.argtypes = ctypes.c_int, [dp, vp, vp, vp, vp, i32, f32, vp, vp, sz, vp]
+        L.fk_decode_step.restype, L.fk_decode_step.argtypes = ctypes.c_int, [dp, vp, vp, vp, vp, vp, vp, vp, vp, i32, f32, vp, vp, sz, vp]
         L.fk_score_kv.restype, L.fk_score_kv.argtypes = ctypes.c_int, [dp, vp, vp, vp, i32, sp, vp, vp]
         L.fk_select_keep.restype, L.fk_select_keep.argtypes = ctypes.c_int, [dp, vp, vp, vp, i32, i32, i32, vp, vp]
         L.fk_compact.restype, L.fk_compact.argtypes = ctypes.c_int, [dp, vp, vp, vp, vp, vp, i32, vp]
@@ -115,12 +116,26 @@ def fk_decode_attn_workspace(desc: CacheDesc, max_len: int) -> int:
     return int(lib().fk_decode_attn_workspace(ctypes.byref(desc.c()), int(max_len)))
 
 
+def new_attn_workspace(desc: CacheDesc) -> "torch.Tensor":
+    """Zero-filled device workspace for fk_decode_attn / fk_decode_step (the counters must start at zero)."""
+    return torch.zeros(max(fk_decode_attn_workspace(desc, desc.capacity), 16), dtype=torch.uint8, device="cuda")
+
+
 def fk_decode_attn(desc: CacheDesc, q, K, V, length, max_len: int, softmax_scale: float, out, workspace,
                    stream=None) -> None:
     nbytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
     _check(lib().fk_decode_attn(ctypes.byref(desc.c()), _ptr(q), _ptr(K), _ptr(V), _ptr(length), int(max_len),
                                 float(softmax_scale), _ptr(out), _ptr(workspace), nbytes, _stream(stream)),
            "fk_decode_attn")
+
+
+def fk_decode_step(desc: CacheDesc, q, K, V, pos, length, k_new, v_new, pos_new, max_len: int, softmax_scale: float,
+                   out, workspace, stream=None) -> None:
+    """fk_append + fk_decode_attn in one launch; max_len bounds len[b] + 1."""
+    nbytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(lib().fk_decode_step(ctypes.byref(desc.c()), _ptr(q), _ptr(K), _ptr(V), _ptr(pos), _ptr(length), _ptr(k_new),
+                                _ptr(v_new), _ptr(pos_new), int(max_len), float(softmax_scale), _ptr(out),
+                                _ptr(workspace), nbytes, _stream(stream)), "fk_decode_step")
 
 
 def fk_score_kv(desc: CacheDesc, K, V, length, max_len: int, W1, b1, W2, b2, scores, stream=None) -> None:

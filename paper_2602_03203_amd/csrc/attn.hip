@@ -1,43 +1,92 @@
-// fk_decode_attn: split-K flash-decode attention over the retained set
-// (Appendix A, "Problem Setup": o_hat = sum_{i in S} softmax_S(s)_i v_i).
+// fk_decode_attn / fk_decode_step: split-K flash-decode attention over the retained set
+// (Appendix A, "Problem Setup": o_hat = sum_{i in S} softmax_S(s)_i v_i), optionally fused with
+// the append of the step's new pair (Section 3.1) so that one decode step is ONE launch.
 //
-// A row (sequence, KV head) is cut into splits of `split_len` keys; one workgroup of four
-// wavefronts handles one split for all g query heads of the group, so K and V are fetched
-// from HBM once per group.  A row of K or V is D*sizeof(T) bytes = LPK lanes x 16 bytes; a
-// wavefront load instruction therefore covers 64/LPK consecutive keys, fully coalesced.
-// Every aligned group of LPK lanes runs its own online softmax over the keys it sees
-// (running maximum m, running sum l, un-normalised accumulator acc for its 16-byte slice
-// of D); the groups of a wavefront, the wavefronts of a workgroup and finally the splits
-// of a row are merged with the log-sum-exp rule.
+// Work decomposition.  A row (sequence, KV head) is cut into `nsplit` splits of `split_len`
+// keys; one workgroup handles one split for all g query heads of the group, so K and V are
+// fetched from HBM once per group.  Inside a workgroup every wavefront walks its own tiles of
+// the split and keeps an online softmax (running maximum m, running sum l, un-normalised
+// accumulator acc); the wavefronts are merged through LDS and the splits of a row through a
+// small record in the workspace, the last workgroup of the row to arrive doing the final
+// log-sum-exp merge and the store of `out` (no second launch).
+//
+// bf16 path.  q.K^T of a 16-key tile is one 16x16x32 MFMA chain (A = the group's query rows,
+// zero padded to 16; B = 16 keys x 32 channels, i.e. 16 contiguous bytes per lane straight from
+// the cache); the softmax runs on the MFMA result layout (one key per lane, 4 heads per lane);
+// the probabilities go through LDS to the P.V layout, where a K/V row is D*2/16 lanes x 16
+// bytes (fully coalesced 128-bit loads) and P.V is plain fp32 FMA.
+// fp32 path.  Same structure with q.K^T as fp32 FMA plus a DPP row reduction.
 #include "fk_common.h"
 
 namespace fk {
 
-static constexpr int kAttnThreads = 256;
-static constexpr int kAttnWaves = kAttnThreads / kWave;
 static constexpr float kNegBig = -1.0e30f;  // "no key seen yet"; exp2(kNegBig - m) == 0
 
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
+typedef __attribute__((ext_vector_type(4))) float f32x4_t;
+union B128 {
+    uint4 u;
+    bf16x8_t v;
+};
+
+// Cross-workgroup traffic (split records, arrival counters) uses agent-scope relaxed atomics:
+// they compile to loads / stores that bypass the per-XCD caches (sc1), which costs nothing next
+// to a device-wide fence (that one writes back and invalidates a whole L2).
+__device__ __forceinline__ void st_agent(float* p, float v) {
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ float ld_agent(const float* p) {
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+// all of this wave's earlier global stores have been acknowledged (vmcnt(0); expcnt, lgkmcnt untouched)
+__device__ __forceinline__ void wait_stores_done() {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+    __builtin_amdgcn_s_waitcnt(0x0F70);
+}
+
+template <int CTRL>
+__device__ __forceinline__ float dpp_max_step(float v) { return fmaxf(v, dpp_f<CTRL>(v)); }
+__device__ __forceinline__ float row16_max(float v) {
+    v = dpp_max_step<DPP_QUAD_XOR1>(v);
+    v = dpp_max_step<DPP_QUAD_XOR2>(v);
+    v = dpp_max_step<DPP_ROW_HALF_MIRROR>(v);
+    v = dpp_max_step<DPP_ROW_MIRROR>(v);
+    return v;
+}
+
+// ---- geometry ------------------------------------------------------------------------------
+template <typename T, int D, int G> struct AttnCfg {
+    static constexpr bool MFMA = sizeof(T) == 2;
+    static constexpr int CH = D * (int)sizeof(T) / 16;      // 16-byte chunks per row = lanes per key (P.V layout)
+    static constexpr int KG = kWave / CH;                   // key groups per wave in the P.V layout
+    static constexpr int WAVES = MFMA ? (G <= 4 ? 8 : 4) : 4;
+    static constexpr int THREADS = WAVES * kWave;
+    static constexpr int KT = MFMA ? 32 : KG * 4;           // keys per wave iteration
+    static constexpr int VU = KT / KG;                      // V (and fp32 K) loads per lane per iteration
+    static constexpr int EPL = Vec16<T>::N;                 // channels per lane
+    static constexpr int GP = G <= 4 ? 4 : 8;               // heads padded to the MFMA result rows in use
+    static constexpr int NG = WAVES * KG;                   // (wave, key group) partial accumulators per workgroup
+    // dynamic LDS: acc [NG][G][D] | m [NG][G] | l [NG][G] | w [NG][G] | M [8] | p [WAVES][KT][GP] | corr [WAVES][GP]
+    static constexpr size_t LDS_BYTES =
+        sizeof(float) * ((size_t)NG * G * D + 3 * (size_t)NG * G + 8 + (size_t)WAVES * KT * GP + (size_t)WAVES * GP + 4);
+};
+
 struct AttnPlan {
-    int split_len;  // keys per split (multiple of the workgroup tile)
+    int split_len;  // keys per split (multiple of the wave tile)
     int nsplit;     // splits per row
 };
 
-// Keys per workgroup iteration: 4 waves x (64/LPK) keys x U loads in flight.
-template <typename T, int D> struct AttnGeom {
-    static constexpr int LPK = D * (int)sizeof(T) / 16;  // lanes per key
-    static constexpr int KPW = kWave / LPK;              // keys per wave load
-    static constexpr int U = 4;                          // loads in flight per lane (K and V each)
-    static constexpr int TILE = kAttnWaves * KPW * U;    // keys per workgroup iteration
-    static constexpr int EPL = Vec16<T>::N;              // elements per lane
-};
+// upper bound on the splits per row: about two workgroups per CU
+static int attn_max_splits(const fk_cache_desc* d) {
+    const int rows = d->batch * d->n_kv_heads;
+    const int want = (2 * 256 + rows - 1) / rows;
+    return want < 1 ? 1 : want;
+}
 
 static AttnPlan attn_plan(const fk_cache_desc* d, int max_len) {
-    const int rows = d->batch * d->n_kv_heads;
-    const int lpk = d->head_dim * (d->dtype == FK_F32 ? 4 : 2) / 16;
-    const int tile = kAttnWaves * (kWave / lpk) * 4;
-    const int target_blocks = 256 * 8;  // a few workgroups per CU in flight
-    int want = (target_blocks + rows - 1) / rows;
-    int max_split = (max_len + tile - 1) / tile;
+    const int tile = 32;
+    int want = attn_max_splits(d);
+    const int max_split = (max_len + tile - 1) / tile;
     if (want > max_split) want = max_split;
     if (want < 1) want = 1;
     int split_len = (max_len + want - 1) / want;
@@ -49,226 +98,415 @@ static AttnPlan attn_plan(const fk_cache_desc* d, int max_len) {
     return p;
 }
 
-// partial record per (row, split, head): acc[D], m, l
-template <typename T, int D, int G>
-__global__ __launch_bounds__(kAttnThreads) void attn_partial_kernel(
-    const T* __restrict__ q, const T* __restrict__ K, const T* __restrict__ V,
-    const int32_t* __restrict__ len, float scale_log2e, int n_kv, int cap, int split_len,
-    int nsplit, float* __restrict__ ws) {
-    using Gm = AttnGeom<T, D>;
-    constexpr int LPK = Gm::LPK, KPW = Gm::KPW, U = Gm::U, EPL = Gm::EPL;
-    const int row = blockIdx.y;
-    const int split = blockIdx.x;
-    const int b = row / n_kv;
-    const int n = min(len[b], cap);
-    const int start = split * split_len;
-    if (start >= n) return;
-    const int end = min(start + split_len, n);
-
-    const int lane = threadIdx.x & (kWave - 1);
-    const int wave = threadIdx.x / kWave;
-    const int kg = lane / LPK;   // key group inside the wave
-    const int dl = lane % LPK;   // which 16-byte slice of the row
-
-    // queries of the group, this lane's slice, pre-multiplied by scale*log2(e)
-    float qf[G][EPL];
-    {
-        const int hkv = row % n_kv;
-        const T* qrow = q + ((size_t)b * n_kv * G + (size_t)hkv * G) * D;
-#pragma unroll
-        for (int h = 0; h < G; ++h) {
-            uint4 r = *reinterpret_cast<const uint4*>(qrow + (size_t)h * D + dl * EPL);
-            Vec16<T>::unpack(r, qf[h]);
-#pragma unroll
-            for (int e = 0; e < EPL; ++e) qf[h][e] *= scale_log2e;
-        }
-    }
-
-    float m[G], l[G], acc[G][EPL];
-#pragma unroll
-    for (int h = 0; h < G; ++h) {
-        m[h] = kNegBig;
-        l[h] = 0.f;
-#pragma unroll
-        for (int e = 0; e < EPL; ++e) acc[h][e] = 0.f;
-    }
-
-    const uint4* Krow = reinterpret_cast<const uint4*>(K + (size_t)row * cap * D);
-    const uint4* Vrow = reinterpret_cast<const uint4*>(V + (size_t)row * cap * D);
-
-    for (int base = start + wave * (KPW * U); base < end; base += kAttnWaves * KPW * U) {
-        uint4 kr[U], vr[U];
-        int key[U];
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            key[u] = base + u * KPW + kg;
-            const int kc = min(key[u], end - 1);  // clamp: always a live slot of this split
-            kr[u] = Krow[(size_t)kc * LPK + dl];
-        }
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const int kc = min(key[u], end - 1);
-            vr[u] = Vrow[(size_t)kc * LPK + dl];
-        }
-        float s[U][G];
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            float kf[EPL];
-            Vec16<T>::unpack(kr[u], kf);
-#pragma unroll
-            for (int h = 0; h < G; ++h) {
-                float d = 0.f;
-#pragma unroll
-                for (int e = 0; e < EPL; ++e) d = fmaf(qf[h][e], kf[e], d);
-                d = group_sum<LPK>(d);
-                s[u][h] = key[u] < end ? d : kNegBig;
-            }
-        }
-        float p[U][G];
-#pragma unroll
-        for (int h = 0; h < G; ++h) {
-            float mn = m[h];
-#pragma unroll
-            for (int u = 0; u < U; ++u) mn = fmaxf(mn, s[u][h]);
-            const float corr = exp2f(m[h] - mn);
-            float ps = 0.f;
-#pragma unroll
-            for (int u = 0; u < U; ++u) {
-                p[u][h] = key[u] < end ? exp2f(s[u][h] - mn) : 0.f;
-                ps += p[u][h];
-            }
-            l[h] = l[h] * corr + ps;
-            m[h] = mn;
-#pragma unroll
-            for (int e = 0; e < EPL; ++e) acc[h][e] *= corr;
-        }
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            float vf[EPL];
-            Vec16<T>::unpack(vr[u], vf);
-#pragma unroll
-            for (int h = 0; h < G; ++h)
-#pragma unroll
-                for (int e = 0; e < EPL; ++e) acc[h][e] = fmaf(p[u][h], vf[e], acc[h][e]);
-        }
-    }
-
-    // merge the key groups of the wave (lanes that hold the same slice of D)
-#pragma unroll
-    for (int off = LPK; off < kWave; off <<= 1) {
-#pragma unroll
-        for (int h = 0; h < G; ++h) {
-            const float mo = __shfl_xor(m[h], off);
-            const float lo = __shfl_xor(l[h], off);
-            const float mn = fmaxf(m[h], mo);
-            const float ca = exp2f(m[h] - mn), cb = exp2f(mo - mn);
-            l[h] = l[h] * ca + lo * cb;
-#pragma unroll
-            for (int e = 0; e < EPL; ++e) {
-                const float ao = __shfl_xor(acc[h][e], off);
-                acc[h][e] = acc[h][e] * ca + ao * cb;
-            }
-            m[h] = mn;
-        }
-    }
-
-    // merge the four waves through LDS
-    __shared__ float s_acc[kAttnWaves][G][D];
-    __shared__ float s_m[kAttnWaves][G];
-    __shared__ float s_l[kAttnWaves][G];
-    if (kg == 0) {
-#pragma unroll
-        for (int h = 0; h < G; ++h) {
-#pragma unroll
-            for (int e = 0; e < EPL; ++e) s_acc[wave][h][dl * EPL + e] = acc[h][e];
-            if (dl == 0) {
-                s_m[wave][h] = m[h];
-                s_l[wave][h] = l[h];
-            }
-        }
-    }
-    __syncthreads();
-    float* rec = ws + ((size_t)row * nsplit + split) * G * (D + 2);
-    for (int idx = threadIdx.x; idx < G * D; idx += kAttnThreads) {
-        const int h = idx / D, d = idx % D;
-        float mn = s_m[0][h];
-#pragma unroll
-        for (int w = 1; w < kAttnWaves; ++w) mn = fmaxf(mn, s_m[w][h]);
-        float a = 0.f, ls = 0.f;
-#pragma unroll
-        for (int w = 0; w < kAttnWaves; ++w) {
-            const float c = exp2f(s_m[w][h] - mn);
-            a += s_acc[w][h][d] * c;
-            ls += s_l[w][h] * c;
-        }
-        rec[(size_t)h * (D + 2) + d] = a;
-        if (d == 0) {
-            rec[(size_t)h * (D + 2) + D] = mn;
-            rec[(size_t)h * (D + 2) + D + 1] = ls;
-        }
-    }
+// workspace: [row counters: rows u32][sequence counters: batch u32] padded to 256 B | records
+static size_t attn_counter_bytes(const fk_cache_desc* d) {
+    const size_t n = (size_t)d->batch * d->n_kv_heads + d->batch;
+    return (n * sizeof(uint32_t) + 255) / 256 * 256;
 }
 
-// out[b][hq][d] = sum_s acc_s[d] 2^(m_s - m*) / sum_s l_s 2^(m_s - m*)
+struct AttnParams {
+    const void* q;
+    void* K;
+    void* V;
+    int32_t* pos;
+    int32_t* len;
+    const void* k_new;  // null: no append
+    const void* v_new;
+    const int32_t* pos_new;
+    float scale_log2e;
+    int n_kv, cap, split_len, nsplit;
+    float* rec;          // [rows][nsplit][G][D + 2]
+    uint32_t* row_cnt;   // [rows], zero between launches
+    uint32_t* seq_cnt;   // [batch], zero between launches
+    void* out;
+};
+
 template <typename T, int D, int G>
-__global__ __launch_bounds__(D) void attn_combine_kernel(const float* __restrict__ ws,
-                                                        const int32_t* __restrict__ len, int n_kv,
-                                                        int cap, int split_len, int nsplit,
-                                                        T* __restrict__ out) {
-    const int row = blockIdx.x / G, h = blockIdx.x % G;
-    const int b = row / n_kv, hkv = row % n_kv;
-    const int d = threadIdx.x;
-    const int n = min(len[b], cap);
-    T* o = out + (((size_t)b * n_kv + hkv) * G + h) * D;
-    if (n <= 0) {
-        store_out(o + d, 0.f);
+__global__ __launch_bounds__((AttnCfg<T, D, G>::THREADS)) void attn_kernel(const AttnParams P) {
+    using C = AttnCfg<T, D, G>;
+    constexpr int CH = C::CH, KG = C::KG, WAVES = C::WAVES, KT = C::KT, VU = C::VU, EPL = C::EPL, GP = C::GP, NG = C::NG;
+    const int row = blockIdx.y, split = blockIdx.x;
+    const int b = row / P.n_kv, hkv = row % P.n_kv;
+    const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
+
+    extern __shared__ __attribute__((aligned(16))) float smem[];
+    float* s_acc = smem;                      // [NG][G][D]
+    float* s_m = s_acc + (size_t)NG * G * D;   // [NG][G]
+    float* s_l = s_m + NG * G;                 // [NG][G]
+    float* s_w = s_l + NG * G;                 // [NG][G] merge weights 2^(m_g - M)
+    float* s_M = s_w + NG * G;                 // [8] merged maximum per head
+    float* s_p = s_M + 8;                      // [WAVES][KT][GP]
+    float* s_corr = s_p + WAVES * KT * GP;     // [WAVES][GP]
+    __shared__ int s_last;
+
+    const bool appending = P.k_new != nullptr;
+    const int n_old = min(max(P.len[b], 0), P.cap);
+    const bool do_append = appending && n_old < P.cap;
+    const int n = n_old + (do_append ? 1 : 0);
+    const int used = (n + P.split_len - 1) / P.split_len;
+    T* out = reinterpret_cast<T*>(P.out) + ((size_t)b * P.n_kv + hkv) * G * D;
+
+    // Every workgroup of a sequence reports to the sequence counter when an append is fused in, so
+    // len[b] is bumped only after all of them have read it.
+    auto seq_arrive = [&]() {
+        if (!appending) return;
+        __syncthreads();
+        if (tid == 0) {
+            const uint32_t total = (uint32_t)gridDim.x * P.n_kv;
+            const uint32_t prev = __hip_atomic_fetch_add(&P.seq_cnt[b], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if (prev == total - 1) {
+                __hip_atomic_store(&P.seq_cnt[b], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                if (do_append) P.len[b] = n;
+            }
+        }
+    };
+
+    if (n == 0) {
+        if (split == 0)
+            for (int i = tid; i < G * D; i += C::THREADS) store_out(out + i, 0.f);
+        seq_arrive();
         return;
     }
-    const int used = (n + split_len - 1) / split_len;
-    const float* rec = ws + (size_t)row * nsplit * G * (D + 2) + (size_t)h * (D + 2);
-    const size_t stride = (size_t)G * (D + 2);
-    float mn = kNegBig;
-    for (int s = 0; s < used; ++s) mn = fmaxf(mn, rec[s * stride + D]);
-    float a = 0.f, ls = 0.f;
-    for (int s = 0; s < used; ++s) {
-        const float c = exp2f(rec[s * stride + D] - mn);
-        a += rec[s * stride + d] * c;
-        ls += rec[s * stride + D + 1] * c;
+    if (split >= used) {
+        seq_arrive();
+        return;
     }
-    store_out(o + d, a / ls);
+    const int start = split * P.split_len;
+    const int end = min(start + P.split_len, n);
+
+    T* Kr = reinterpret_cast<T*>(P.K) + (size_t)row * P.cap * D;
+    T* Vr = reinterpret_cast<T*>(P.V) + (size_t)row * P.cap * D;
+    if (do_append && n_old >= start && n_old < end) {
+        // this workgroup owns the slot of the new pair: write it, then read it back like any other
+        if (tid < CH) {
+            reinterpret_cast<uint4*>(Kr + (size_t)n_old * D)[tid] =
+                reinterpret_cast<const uint4*>(reinterpret_cast<const T*>(P.k_new) + (size_t)row * D)[tid];
+        } else if (tid < 2 * CH) {
+            reinterpret_cast<uint4*>(Vr + (size_t)n_old * D)[tid - CH] =
+                reinterpret_cast<const uint4*>(reinterpret_cast<const T*>(P.v_new) + (size_t)row * D)[tid - CH];
+        } else if (tid == 2 * CH) {
+            P.pos[(size_t)row * P.cap + n_old] = P.pos_new[b];
+        }
+        __syncthreads();
+    }
+    const uint4* Krow = reinterpret_cast<const uint4*>(Kr);
+    const uint4* Vrow = reinterpret_cast<const uint4*>(Vr);
+    const T* qrow = reinterpret_cast<const T*>(P.q) + ((size_t)b * P.n_kv + hkv) * G * D;
+
+    const int dl = lane % CH;   // 16-byte chunk of the row (P.V layout)
+    const int kgv = lane / CH;  // key group (P.V layout)
+    float acc[G][EPL];
+#pragma unroll
+    for (int h = 0; h < G; ++h)
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) acc[h][e] = 0.f;
+
+    if constexpr (C::MFMA) {
+        constexpr int KS = D / 32;  // MFMA k-steps
+        const int n16 = lane & 15, quad = lane >> 4;
+        B128 qa[KS];
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            if (n16 < G) qa[ks].u = *reinterpret_cast<const uint4*>(qrow + (size_t)n16 * D + ks * 32 + quad * 8);
+            else qa[ks].u = make_uint4(0, 0, 0, 0);
+        }
+        float m_run[4], l_run[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            m_run[i] = kNegBig;
+            l_run[i] = 0.f;
+        }
+        float* my_p = s_p + (size_t)wave * KT * GP;
+        float* my_corr = s_corr + wave * GP;
+
+        for (int base = start + wave * KT; base < end; base += WAVES * KT) {
+            B128 kb[2][KS];
+            uint4 vr[VU];
+#pragma unroll
+            for (int nt = 0; nt < 2; ++nt) {
+                const int kc = min(base + nt * 16 + n16, end - 1);  // clamp: always a live slot
+#pragma unroll
+                for (int ks = 0; ks < KS; ++ks) kb[nt][ks].u = Krow[(size_t)kc * CH + ks * 4 + quad];
+            }
+#pragma unroll
+            for (int u = 0; u < VU; ++u) {
+                const int kc = min(base + u * KG + kgv, end - 1);
+                vr[u] = Vrow[(size_t)kc * CH + dl];
+            }
+            f32x4_t c[2];
+#pragma unroll
+            for (int nt = 0; nt < 2; ++nt) {
+                c[nt] = (f32x4_t){0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int ks = 0; ks < KS; ++ks)
+                    c[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(qa[ks].v, kb[nt][ks].v, c[nt], 0, 0, 0);
+            }
+            // result layout: lane = key n16 of tile nt, element i = head quad*4 + i
+            float p[2][4], corr[4];
+            bool changed = false;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const float s0 = (base + n16 < end) ? c[0][i] * P.scale_log2e : kNegBig;
+                const float s1 = (base + 16 + n16 < end) ? c[1][i] * P.scale_log2e : kNegBig;
+                const float mn = fmaxf(m_run[i], row16_max(fmaxf(s0, s1)));
+                changed |= mn > m_run[i];
+                corr[i] = exp2f(m_run[i] - mn);
+                p[0][i] = exp2f(s0 - mn);
+                p[1][i] = exp2f(s1 - mn);
+                l_run[i] = l_run[i] * corr[i] + p[0][i] + p[1][i];
+                m_run[i] = mn;
+            }
+            const bool any_changed = __any(changed);
+            if (quad * 4 < GP) {
+                *reinterpret_cast<float4*>(my_p + (size_t)n16 * GP + quad * 4) = make_float4(p[0][0], p[0][1], p[0][2], p[0][3]);
+                *reinterpret_cast<float4*>(my_p + (size_t)(16 + n16) * GP + quad * 4) = make_float4(p[1][0], p[1][1], p[1][2], p[1][3]);
+                if (n16 == 0) *reinterpret_cast<float4*>(my_corr + quad * 4) = make_float4(corr[0], corr[1], corr[2], corr[3]);
+            }
+            __builtin_amdgcn_wave_barrier();
+            if (any_changed) {  // the running maximum moved: rescale what has been accumulated
+                float cr[GP];
+#pragma unroll
+                for (int h4 = 0; h4 < GP; h4 += 4) {
+                    const float4 t = *reinterpret_cast<const float4*>(my_corr + h4);
+                    cr[h4] = t.x; cr[h4 + 1] = t.y; cr[h4 + 2] = t.z; cr[h4 + 3] = t.w;
+                }
+#pragma unroll
+                for (int h = 0; h < G; ++h)
+#pragma unroll
+                    for (int e = 0; e < EPL; ++e) acc[h][e] *= cr[h];
+            }
+#pragma unroll
+            for (int u = 0; u < VU; ++u) {
+                float pp[GP];
+#pragma unroll
+                for (int h4 = 0; h4 < GP; h4 += 4) {
+                    const float4 t = *reinterpret_cast<const float4*>(my_p + (size_t)(u * KG + kgv) * GP + h4);
+                    pp[h4] = t.x; pp[h4 + 1] = t.y; pp[h4 + 2] = t.z; pp[h4 + 3] = t.w;
+                }
+                float vf[EPL];
+                Vec16<T>::unpack(vr[u], vf);
+#pragma unroll
+                for (int e = 0; e < EPL; ++e)
+#pragma unroll
+                    for (int h = 0; h < G; ++h) acc[h][e] = fmaf(pp[h], vf[e], acc[h][e]);
+            }
+            __builtin_amdgcn_wave_barrier();
+        }
+        // publish: every (wave, key group) its accumulator; m is uniform in the wave, l is the
+        // sum over the 16 key lanes and is credited to key group 0
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const float ls = group_sum<16>(l_run[i]);
+            const int h = quad * 4 + i;
+            if (n16 == 0 && h < G) {
+#pragma unroll
+                for (int g2 = 0; g2 < KG; ++g2) {
+                    s_m[(wave * KG + g2) * G + h] = m_run[i];
+                    s_l[(wave * KG + g2) * G + h] = g2 == 0 ? ls : 0.f;
+                }
+            }
+        }
+    } else {
+        // fp32: every key group (CH lanes) keeps its own online softmax over the keys it sees
+        float qf[G][EPL];
+#pragma unroll
+        for (int h = 0; h < G; ++h) {
+            Vec16<T>::unpack(*reinterpret_cast<const uint4*>(qrow + (size_t)h * D + dl * EPL), qf[h]);
+#pragma unroll
+            for (int e = 0; e < EPL; ++e) qf[h][e] *= P.scale_log2e;
+        }
+        float m[G], l[G];
+#pragma unroll
+        for (int h = 0; h < G; ++h) {
+            m[h] = kNegBig;
+            l[h] = 0.f;
+        }
+        for (int base = start + wave * KT; base < end; base += WAVES * KT) {
+            uint4 kr[VU], vr[VU];
+            int key[VU];
+#pragma unroll
+            for (int u = 0; u < VU; ++u) {
+                key[u] = base + u * KG + kgv;
+                kr[u] = Krow[(size_t)min(key[u], end - 1) * CH + dl];
+            }
+#pragma unroll
+            for (int u = 0; u < VU; ++u) vr[u] = Vrow[(size_t)min(key[u], end - 1) * CH + dl];
+            float s[VU][G];
+#pragma unroll
+            for (int u = 0; u < VU; ++u) {
+                float kf[EPL];
+                Vec16<T>::unpack(kr[u], kf);
+#pragma unroll
+                for (int h = 0; h < G; ++h) {
+                    float d = 0.f;
+#pragma unroll
+                    for (int e = 0; e < EPL; ++e) d = fmaf(qf[h][e], kf[e], d);
+                    d = group_sum<CH>(d);
+                    s[u][h] = key[u] < end ? d : kNegBig;
+                }
+            }
+            float p[VU][G];
+#pragma unroll
+            for (int h = 0; h < G; ++h) {
+                float mn = m[h];
+#pragma unroll
+                for (int u = 0; u < VU; ++u) mn = fmaxf(mn, s[u][h]);
+                const float corr = exp2f(m[h] - mn);
+                float ps = 0.f;
+#pragma unroll
+                for (int u = 0; u < VU; ++u) {
+                    p[u][h] = key[u] < end ? exp2f(s[u][h] - mn) : 0.f;
+                    ps += p[u][h];
+                }
+                l[h] = l[h] * corr + ps;
+                m[h] = mn;
+#pragma unroll
+                for (int e = 0; e < EPL; ++e) acc[h][e] *= corr;
+            }
+#pragma unroll
+            for (int u = 0; u < VU; ++u) {
+                float vf[EPL];
+                Vec16<T>::unpack(vr[u], vf);
+#pragma unroll
+                for (int h = 0; h < G; ++h)
+#pragma unroll
+                    for (int e = 0; e < EPL; ++e) acc[h][e] = fmaf(p[u][h], vf[e], acc[h][e]);
+            }
+        }
+        if (dl == 0) {
+#pragma unroll
+            for (int h = 0; h < G; ++h) {
+                s_m[(wave * KG + kgv) * G + h] = m[h];
+                s_l[(wave * KG + kgv) * G + h] = l[h];
+            }
+        }
+    }
+
+    // ---- merge the (wave, key group) partials of the workgroup ---------------------------------
+    {
+        float* dst = s_acc + ((size_t)(wave * KG + kgv) * G) * D + dl * EPL;
+#pragma unroll
+        for (int h = 0; h < G; ++h)
+#pragma unroll
+            for (int e4 = 0; e4 < EPL; e4 += 4)
+                *reinterpret_cast<float4*>(dst + (size_t)h * D + e4) =
+                    make_float4(acc[h][e4], acc[h][e4 + 1], acc[h][e4 + 2], acc[h][e4 + 3]);
+    }
+    __syncthreads();
+    for (int t = tid; t < NG * G; t += C::THREADS) {  // weight of every partial: 2^(m_g - M)
+        const int h = t % G;
+        float mn = kNegBig;
+#pragma unroll 8
+        for (int g2 = 0; g2 < NG; ++g2) mn = fmaxf(mn, s_m[g2 * G + h]);
+        s_w[t] = exp2f(s_m[t] - mn);
+        if (t < G) s_M[t] = mn;
+    }
+    __syncthreads();
+    float* rec = P.rec + ((size_t)row * P.nsplit + split) * G * (D + 2);
+    for (int idx = tid; idx < G * D; idx += C::THREADS) {
+        const int h = idx / D, d = idx % D;
+        const float mn = s_M[h];
+        float a = 0.f, ls = 0.f;
+#pragma unroll 8
+        for (int g2 = 0; g2 < NG; ++g2) a = fmaf(s_acc[((size_t)g2 * G + h) * D + d], s_w[g2 * G + h], a);
+        if (d == 0 || used == 1) {
+#pragma unroll 8
+            for (int g2 = 0; g2 < NG; ++g2) ls = fmaf(s_l[g2 * G + h], s_w[g2 * G + h], ls);
+        }
+        if (used == 1) {
+            store_out(out + idx, a / ls);
+        } else {
+            st_agent(rec + (size_t)h * (D + 2) + d, a);
+            if (d == 0) {
+                st_agent(rec + (size_t)h * (D + 2) + D, mn);
+                st_agent(rec + (size_t)h * (D + 2) + D + 1, ls);
+            }
+        }
+    }
+    if (used > 1) {
+        // last workgroup of the row merges the splits: out = sum_s acc_s 2^(m_s - m*) / sum_s l_s 2^(m_s - m*)
+        wait_stores_done();
+        __syncthreads();
+        if (tid == 0) {
+            const uint32_t prev = __hip_atomic_fetch_add(&P.row_cnt[row], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            s_last = prev == (uint32_t)used - 1;
+            if (s_last) __hip_atomic_store(&P.row_cnt[row], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+        __syncthreads();
+        if (s_last) {
+            const float* r0 = P.rec + (size_t)row * P.nsplit * G * (D + 2);
+            const size_t stride = (size_t)G * (D + 2);
+            for (int idx = tid; idx < G * D; idx += C::THREADS) {
+                const int h = idx / D, d = idx % D;
+                const float* r = r0 + (size_t)h * (D + 2);
+                float mn = kNegBig;
+                for (int s = 0; s < used; ++s) mn = fmaxf(mn, ld_agent(r + s * stride + D));
+                float a = 0.f, ls = 0.f;
+                for (int s = 0; s < used; ++s) {
+                    const float cw = exp2f(ld_agent(r + s * stride + D) - mn);
+                    a = fmaf(ld_agent(r + s * stride + d), cw, a);
+                    ls = fmaf(ld_agent(r + s * stride + D + 1), cw, ls);
+                }
+                store_out(out + idx, a / ls);
+            }
+        }
+    }
+    seq_arrive();
 }
 
 template <typename T, int D, int G>
-static fk_status attn_launch(const fk_cache_desc* d, const void* q, const void* K, const void* V,
-                             const int32_t* len, int max_len, float scale, void* out, float* ws,
-                             hipStream_t st) {
+static fk_status attn_launch(const fk_cache_desc* d, const AttnParams& base, int max_len, void* ws, hipStream_t st) {
+    using C = AttnCfg<T, D, G>;
     const AttnPlan p = attn_plan(d, max_len);
     const int rows = d->batch * d->n_kv_heads;
-    const float scale_log2e = scale * 1.4426950408889634f;
-    dim3 grid(p.nsplit, rows);
-    hipLaunchKernelGGL((attn_partial_kernel<T, D, G>), grid, dim3(kAttnThreads), 0, st,
-                       (const T*)q, (const T*)K, (const T*)V, len, scale_log2e, d->n_kv_heads,
-                       d->capacity, p.split_len, p.nsplit, ws);
-    hipLaunchKernelGGL((attn_combine_kernel<T, D, G>), dim3(rows * G), dim3(D), 0, st, ws, len,
-                       d->n_kv_heads, d->capacity, p.split_len, p.nsplit, (T*)out);
+    AttnParams P = base;
+    P.split_len = p.split_len;
+    P.nsplit = p.nsplit;
+    P.row_cnt = reinterpret_cast<uint32_t*>(ws);
+    P.seq_cnt = P.row_cnt + rows;
+    P.rec = reinterpret_cast<float*>(reinterpret_cast<char*>(ws) + attn_counter_bytes(d));
+    auto kern = attn_kernel<T, D, G>;
+    static bool attr_set = false;  // per template instantiation
+    if (!attr_set) {
+        if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)C::LDS_BYTES) != hipSuccess)
+            return FK_ERR_LAUNCH;
+        attr_set = true;
+    }
+    hipLaunchKernelGGL(kern, dim3(p.nsplit, rows), dim3(C::THREADS), C::LDS_BYTES, st, P);
     return launch_status();
 }
 
 template <typename T, int D>
-static fk_status attn_dispatch_g(int g, const fk_cache_desc* d, const void* q, const void* K,
-                                 const void* V, const int32_t* len, int max_len, float scale,
-                                 void* out, float* ws, hipStream_t st) {
+static fk_status attn_dispatch_g(int g, const fk_cache_desc* d, const AttnParams& P, int max_len, void* ws, hipStream_t st) {
     switch (g) {
-        case 1: return attn_launch<T, D, 1>(d, q, K, V, len, max_len, scale, out, ws, st);
-        case 2: return attn_launch<T, D, 2>(d, q, K, V, len, max_len, scale, out, ws, st);
-        case 3: return attn_launch<T, D, 3>(d, q, K, V, len, max_len, scale, out, ws, st);
-        case 4: return attn_launch<T, D, 4>(d, q, K, V, len, max_len, scale, out, ws, st);
-        case 5: return attn_launch<T, D, 5>(d, q, K, V, len, max_len, scale, out, ws, st);
-        case 6: return attn_launch<T, D, 6>(d, q, K, V, len, max_len, scale, out, ws, st);
-        case 7: return attn_launch<T, D, 7>(d, q, K, V, len, max_len, scale, out, ws, st);
-        case 8: return attn_launch<T, D, 8>(d, q, K, V, len, max_len, scale, out, ws, st);
+        case 1: return attn_launch<T, D, 1>(d, P, max_len, ws, st);
+        case 2: return attn_launch<T, D, 2>(d, P, max_len, ws, st);
+        case 3: return attn_launch<T, D, 3>(d, P, max_len, ws, st);
+        case 4: return attn_launch<T, D, 4>(d, P, max_len, ws, st);
+        case 5: return attn_launch<T, D, 5>(d, P, max_len, ws, st);
+        case 6: return attn_launch<T, D, 6>(d, P, max_len, ws, st);
+        case 7: return attn_launch<T, D, 7>(d, P, max_len, ws, st);
+        case 8: return attn_launch<T, D, 8>(d, P, max_len, ws, st);
     }
     return FK_ERR_UNSUPPORTED;
+}
+
+static fk_status attn_entry(const fk_cache_desc* desc, AttnParams P, int max_len, float softmax_scale, void* workspace,
+                            size_t workspace_bytes, void* stream) {
+    if (max_len <= 0 || max_len > desc->capacity) return FK_ERR_INVALID_ARG;
+    const size_t need = fk_decode_attn_workspace(desc, max_len);
+    if (!workspace || workspace_bytes < need || !aligned16(workspace)) return FK_ERR_WORKSPACE;
+    const int g = desc->n_q_heads / desc->n_kv_heads;
+    P.scale_log2e = softmax_scale * 1.4426950408889634f;
+    P.n_kv = desc->n_kv_heads;
+    P.cap = desc->capacity;
+    hipStream_t st = (hipStream_t)stream;
+    if (desc->dtype == FK_F32) {
+        if (desc->head_dim == 64) return attn_dispatch_g<float, 64>(g, desc, P, max_len, workspace, st);
+        return attn_dispatch_g<float, 128>(g, desc, P, max_len, workspace, st);
+    }
+    if (desc->head_dim == 64) return attn_dispatch_g<bf16_t, 64>(g, desc, P, max_len, workspace, st);
+    return attn_dispatch_g<bf16_t, 128>(g, desc, P, max_len, workspace, st);
 }
 
 }  // namespace fk
@@ -277,29 +515,46 @@ using namespace fk;
 
 extern "C" size_t fk_decode_attn_workspace(const fk_cache_desc* desc, int32_t max_len) {
     if (check_desc(desc) != FK_OK || max_len <= 0 || max_len > desc->capacity) return 0;
-    const AttnPlan p = attn_plan(desc, max_len);
+    // sized for the largest split count any max_len can get, so one workspace serves every call
     const size_t g = desc->n_q_heads / desc->n_kv_heads;
-    return (size_t)desc->batch * desc->n_kv_heads * p.nsplit * g * (desc->head_dim + 2) * sizeof(float);
+    return attn_counter_bytes(desc) +
+           (size_t)desc->batch * desc->n_kv_heads * attn_max_splits(desc) * g * (desc->head_dim + 2) * sizeof(float);
 }
 
-extern "C" fk_status fk_decode_attn(const fk_cache_desc* desc, const void* q, const void* K,
-                                    const void* V, const int32_t* len, int32_t max_len,
-                                    float softmax_scale, void* out, void* workspace,
-                                    size_t workspace_bytes, void* stream) {
+extern "C" fk_status fk_decode_attn(const fk_cache_desc* desc, const void* q, const void* K, const void* V,
+                                    const int32_t* len, int32_t max_len, float softmax_scale, void* out,
+                                    void* workspace, size_t workspace_bytes, void* stream) {
     fk_status s = check_desc(desc);
     if (s != FK_OK) return s;
     if (!q || !K || !V || !len || !out) return FK_ERR_INVALID_ARG;
-    if (max_len <= 0 || max_len > desc->capacity) return FK_ERR_INVALID_ARG;
     if (!aligned16(q) || !aligned16(K) || !aligned16(V) || !aligned16(out)) return FK_ERR_INVALID_ARG;
-    const size_t need = fk_decode_attn_workspace(desc, max_len);
-    if (!workspace || workspace_bytes < need || !aligned16(workspace)) return FK_ERR_WORKSPACE;
-    const int g = desc->n_q_heads / desc->n_kv_heads;
-    hipStream_t st = (hipStream_t)stream;
-    float* ws = (float*)workspace;
-    if (desc->dtype == FK_F32) {
-        if (desc->head_dim == 64) return attn_dispatch_g<float, 64>(g, desc, q, K, V, len, max_len, softmax_scale, out, ws, st);
-        return attn_dispatch_g<float, 128>(g, desc, q, K, V, len, max_len, softmax_scale, out, ws, st);
-    }
-    if (desc->head_dim == 64) return attn_dispatch_g<bf16_t, 64>(g, desc, q, K, V, len, max_len, softmax_scale, out, ws, st);
-    return attn_dispatch_g<bf16_t, 128>(g, desc, q, K, V, len, max_len, softmax_scale, out, ws, st);
+    AttnParams P = {};
+    P.q = q;
+    P.K = const_cast<void*>(K);
+    P.V = const_cast<void*>(V);
+    P.len = const_cast<int32_t*>(len);
+    P.out = out;
+    return attn_entry(desc, P, max_len, softmax_scale, workspace, workspace_bytes, stream);
+}
+
+extern "C" fk_status fk_decode_step(const fk_cache_desc* desc, const void* q, void* K, void* V, int32_t* pos,
+                                    int32_t* len, const void* k_new, const void* v_new, const int32_t* pos_new,
+                                    int32_t max_len, float softmax_scale, void* out, void* workspace,
+                                    size_t workspace_bytes, void* stream) {
+    fk_status s = check_desc(desc);
+    if (s != FK_OK) return s;
+    if (!q || !K || !V || !pos || !len || !k_new || !v_new || !pos_new || !out) return FK_ERR_INVALID_ARG;
+    if (!aligned16(q) || !aligned16(K) || !aligned16(V) || !aligned16(out) || !aligned16(k_new) || !aligned16(v_new))
+        return FK_ERR_INVALID_ARG;
+    AttnParams P = {};
+    P.q = q;
+    P.K = K;
+    P.V = V;
+    P.pos = pos;
+    P.len = len;
+    P.k_new = k_new;
+    P.v_new = v_new;
+    P.pos_new = pos_new;
+    P.out = out;
+    return attn_entry(desc, P, max_len, softmax_scale, workspace, workspace_bytes, stream);
 }

@@ -50,7 +50,7 @@ __global__ __launch_bounds__(kCompactThreads) void compact_kernel(uint4* __restr
                                                                   int cap, int budget, int chunks) {
     const int row = blockIdx.x;
     const int b = row / n_kv;
-    const int n = len[b];
+    const int n = min(len[b], cap);
     if (n <= budget) return;
     const int32_t* kp = keep + (size_t)row * budget;
     if (blockIdx.y == 2) {

@@ -33,7 +33,7 @@ class DevCache:
         self.desc = fk.CacheDesc(Bt, n_q_heads, Hkv, D, cap, c.dtype)
         self.K, self.V = to_dev(c.K), to_dev(c.V)
         self.pos, self.len = to_dev(c.pos), to_dev(c.len)
-        self.ws = torch.empty(max(fk.fk_decode_attn_workspace(self.desc, cap), 16), dtype=torch.uint8, device="cuda")
+        self.ws = fk.new_attn_workspace(self.desc)
         self.out = torch.empty((Bt, n_q_heads, D), dtype=self.desc.torch_dtype, device="cuda")
         self.scores = torch.full((Bt, Hkv, cap), float("nan"), dtype=torch.float32, device="cuda")
 

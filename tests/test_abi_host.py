@@ -43,6 +43,7 @@ def test_argument_validation_without_gpu(fklib):
     L = fklib.lib()
     D = fklib.fk_cache_desc
     good = D(2, 8, 2, 128, 512, fklib.FK_BF16)
+    assert L.fk_decode_step(ctypes.byref(good), 0, 0, 0, 0, 0, 0, 0, 0, 512, 1.0, 0, 0, 0, 0) == fklib.FK_ERR_INVALID_ARG
     # null buffers
     assert L.fk_append(ctypes.byref(good), 0, 0, 0, 0, 0, 0, 0, 0) == fklib.FK_ERR_INVALID_ARG
     assert L.fk_decode_attn(ctypes.byref(good), 0, 0, 0, 0, 512, 1.0, 0, 0, 0, 0) == fklib.FK_ERR_INVALID_ARG

@@ -178,6 +178,39 @@ def test_compact_bit_exact(gpu, ora, dtype, D, Bt, Hkv, cap, lens, budget):
         assert np.array_equal(got.K, host.K) and np.array_equal(got.V, host.V)
 
 
+@pytest.mark.parametrize("dtype,D,Hq,Hkv,cap,lens", [
+    ("bf16", 128, 32, 8, 2176, [2175, 2048, 0, 1087, 1088]),      # split boundaries, empty row, last free slot
+    ("bf16", 128, 28, 4, 600, [600, 599, 31, 32]),                # one sequence is full: no append, attention still runs
+    ("f32", 64, 8, 2, 160, [159, 0, 77]),
+    ("bf16", 64, 4, 2, 100, [5, 99]),
+])
+def test_decode_step_equals_append_then_attention(gpu, ora, dtype, D, Hq, Hkv, cap, lens):
+    """The fused launch against the oracle's append followed by the oracle's attention; cache bits exact."""
+    import paper_2602_03203_amd as fk
+    Bt = len(lens)
+    print(f"decode_step case {dtype} D={D} Hq={Hq} Hkv={Hkv} cap={cap} lens={lens}", flush=True)
+    c = random_cache(ora, 7000 + cap, dtype, Bt, Hkv, cap, D, lens=lens)
+    dev = gpu.DevCache(c, Hq)
+    scale = D ** -0.5
+    for rep in range(3):                                      # consecutive steps reuse the workspace counters
+        q = random_q(7001 + rep, dtype, Bt, Hq, D)
+        k_new = random_q(7101 + rep, dtype, Bt, Hkv, D)
+        v_new = random_q(7201 + rep, dtype, Bt, Hkv, D)
+        pos_new = (np.arange(Bt) + 10000 + rep).astype(np.int32)
+        fk.fk_decode_step(dev.desc, gpu.to_dev(q), dev.K, dev.V, dev.pos, dev.len, gpu.to_dev(k_new), gpu.to_dev(v_new),
+                          gpu.to_dev(pos_new), cap, scale, dev.out, dev.ws)
+        for b in range(Bt):
+            if c.len[b] < cap:
+                sub = ora.Cache(dtype, c.K[b:b + 1], c.V[b:b + 1], c.pos[b:b + 1], c.len[b:b + 1])   # views: appended in place
+                ora.append(sub, k_new[b:b + 1], v_new[b:b + 1], pos_new[b:b + 1])
+        ref = ora.decode_attn(c, q, scale)
+        gpu.assert_attn_close(gpu.out_to_f64(dev.out), ref, dtype, f"fused step {rep}")
+        got = dev.host(ora)
+        assert np.array_equal(got.len, c.len) and np.array_equal(got.pos, c.pos)
+        assert np.array_equal(got.K, c.K) and np.array_equal(got.V, c.V)
+    assert int(torch.count_nonzero(dev.ws[:4 * (Bt * Hkv + Bt)])) == 0        # counters are back to zero
+
+
 @pytest.mark.parametrize("dtype,D", [("f32", 64), ("bf16", 128), ("bf16", 64), ("f32", 128)])
 def test_append_bit_exact(gpu, ora, dtype, D):
     import paper_2602_03203_amd as fk

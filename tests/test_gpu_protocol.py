@@ -26,7 +26,7 @@ def gpu():
     return gpu_util
 
 
-def lockstep(gpu, ora, w, n_steps, sample_rows=None, scale=None, check_every=1):
+def lockstep(gpu, ora, w, n_steps, sample_rows=None, scale=None, check_every=1, fused=True):
     """Run the device on the whole workload and the oracle on `sample_rows` [(b, h), ...]
     (None = every row).  Returns the number of events checked."""
     import paper_2602_03203_amd as fk
@@ -52,9 +52,13 @@ def lockstep(gpu, ora, w, n_steps, sample_rows=None, scale=None, check_every=1):
     events = 0
     max_len = int(lens0.max())
     for t in range(n_steps):
-        fk.fk_append(dev.desc, dev.K, dev.V, dev.pos, dev.len, dk[t], dv[t], dp[t])
         max_len += 1
-        fk.fk_decode_attn(dev.desc, dq[t], dev.K, dev.V, dev.len, min(max_len, w.capacity), scale, dev.out, dev.ws)
+        if fused:      # one launch: append + attention (what bench.py times)
+            fk.fk_decode_step(dev.desc, dq[t], dev.K, dev.V, dev.pos, dev.len, dk[t], dv[t], dp[t], min(max_len, w.capacity),
+                              scale, dev.out, dev.ws)
+        else:
+            fk.fk_append(dev.desc, dev.K, dev.V, dev.pos, dev.len, dk[t], dv[t], dp[t])
+            fk.fk_decode_attn(dev.desc, dq[t], dev.K, dev.V, dev.len, min(max_len, w.capacity), scale, dev.out, dev.ws)
         for (b, h), c in subs.items():
             ora.append(c, k_all[t, b:b + 1, h:h + 1], v_all[t, b:b + 1, h:h + 1], p_all[t, b:b + 1])
         if t % check_every == 0 or (t + 1) % L == 0:
@@ -102,10 +106,11 @@ def lockstep(gpu, ora, w, n_steps, sample_rows=None, scale=None, check_every=1):
     return events
 
 
-def test_tiny_workload_full_run(gpu, ora):
+@pytest.mark.parametrize("fused", [True, False])
+def test_tiny_workload_full_run(gpu, ora, fused):
     """configs[0] end to end: 512 steps, 16 event clocks (14 with rows over budget), every row."""
     w = si.config(0)
-    assert lockstep(gpu, ora, w, w.steps) == 16
+    assert lockstep(gpu, ora, w, w.steps, fused=fused) == 16
 
 
 def test_tiny_workload_peaked_softmax(gpu, ora):
@@ -120,7 +125,8 @@ def test_qwen3_4b_layer_shape_sampled_rows(gpu, ora):
     w = si.config(1).scaled(prompt=1920)
     rows = [(0, 0), (5, 3), (11, 6), (15, 7)]
     for scale in (w.softmax_scale, 128.0 ** 0.5):       # near-uniform and unit-variance logits
-        assert lockstep(gpu, ora, w, 400 if scale == w.softmax_scale else 260, sample_rows=rows, scale=scale, check_every=16) >= 2
+        assert lockstep(gpu, ora, w, 400 if scale == w.softmax_scale else 260, sample_rows=rows, scale=scale, check_every=16,
+                        fused=scale == w.softmax_scale) >= 2
 
 
 def test_gqa7_mixture_sampled_rows(gpu, ora):
