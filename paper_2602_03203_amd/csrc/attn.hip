@@ -10,12 +10,17 @@
 // small record in the workspace, the last workgroup of the row to arrive doing the final
 // log-sum-exp merge and the store of `out` (no second launch).
 //
-// bf16 path.  q.K^T of a 16-key tile is one 16x16x32 MFMA chain (A = the group's query rows,
-// zero padded to 16; B = 16 keys x 32 channels, i.e. 16 contiguous bytes per lane straight from
-// the cache); the softmax runs on the MFMA result layout (one key per lane, 4 heads per lane);
-// the probabilities go through LDS to the P.V layout, where a K/V row is D*2/16 lanes x 16
-// bytes (fully coalesced 128-bit loads) and P.V is plain fp32 FMA.
-// fp32 path.  Same structure with q.K^T as fp32 FMA plus a DPP row reduction.
+// bf16, D = 128.  K and V tiles of 32 keys are fetched with fully coalesced 128-bit loads (a row is
+// 16 lanes x 16 bytes, four rows per wavefront instruction).  The K tile is staged in LDS (padded
+// rows) and read back in the MFMA operand layout (one key per lane, 8 consecutive channels), so
+// q.K^T is a 16x16x32 MFMA chain with A = the group's query rows zero padded to 16.  The softmax
+// runs on the MFMA result layout (one key per lane, 4 heads per lane).  The probabilities, rounded
+// to bf16 (the same rounded values feed the normaliser), go through LDS into the A operand of the
+// second contraction; its B operand is the V tile, transposed 8x8 inside each lane's registers
+// (byte permutes, no cross-lane traffic), so P.V is MFMA too and the accumulator lives in the
+// MFMA result layout.  The vector ALUs only do the softmax.
+// bf16, D = 64.  q.K^T on MFMA with the K operand loaded directly, P.V as fp32 FMA.
+// fp32.  q.K^T as fp32 FMA plus a DPP row reduction, P.V as fp32 FMA.
 #include "fk_common.h"
 
 namespace fk {
@@ -57,18 +62,23 @@ __device__ __forceinline__ float row16_max(float v) {
 // ---- geometry ------------------------------------------------------------------------------
 template <typename T, int D, int G> struct AttnCfg {
     static constexpr bool MFMA = sizeof(T) == 2;
+    static constexpr bool PVM = MFMA && D == 128;           // P.V on MFMA as well
     static constexpr int CH = D * (int)sizeof(T) / 16;      // 16-byte chunks per row = lanes per key (P.V layout)
     static constexpr int KG = kWave / CH;                   // key groups per wave in the P.V layout
-    static constexpr int WAVES = MFMA ? (G <= 4 ? 8 : 4) : 4;
+    static constexpr int WAVES = PVM ? 8 : (MFMA ? (G <= 4 ? 8 : 4) : 4);
     static constexpr int THREADS = WAVES * kWave;
     static constexpr int KT = MFMA ? 32 : KG * 4;           // keys per wave iteration
     static constexpr int VU = KT / KG;                      // V (and fp32 K) loads per lane per iteration
     static constexpr int EPL = Vec16<T>::N;                 // channels per lane
     static constexpr int GP = G <= 4 ? 4 : 8;               // heads padded to the MFMA result rows in use
-    static constexpr int NG = WAVES * KG;                   // (wave, key group) partial accumulators per workgroup
+    static constexpr int NG = PVM ? WAVES : WAVES * KG;     // partial accumulators per workgroup
+    static constexpr int PS = KT + 8;                       // PVM: bf16 row stride of the P tile in LDS
+    static constexpr int KRS = 272;                         // PVM: padded byte stride of a K row in LDS
     // dynamic LDS: acc [NG][G][D] | m [NG][G] | l [NG][G] | w [NG][G] | M [8] | p [WAVES][KT][GP] | corr [WAVES][GP]
+    //              | PVM only: K tiles [WAVES][KT][KRS] bytes (the fp32 p area holds the bf16 P tile)
     static constexpr size_t LDS_BYTES =
-        sizeof(float) * ((size_t)NG * G * D + 3 * (size_t)NG * G + 8 + (size_t)WAVES * KT * GP + (size_t)WAVES * GP + 4);
+        sizeof(float) * ((size_t)NG * G * D + 3 * (size_t)NG * G + 8 + (size_t)WAVES * KT * GP + (size_t)WAVES * GP + 4) +
+        (PVM ? (size_t)WAVES * KT * KRS : 0);
 };
 
 struct AttnPlan {
@@ -76,10 +86,17 @@ struct AttnPlan {
     int nsplit;     // splits per row
 };
 
-// upper bound on the splits per row: about two workgroups per CU
+// Upper bound on the splits per row.  The bf16 D = 128 kernel saturates HBM from 128 workgroups of
+// eight wavefronts, so rows are split only when there are fewer rows than that (no split = no
+// cross-workgroup merge at the end of the launch); the other kernels want about two per CU.
 static int attn_max_splits(const fk_cache_desc* d) {
     const int rows = d->batch * d->n_kv_heads;
-    const int want = (2 * 256 + rows - 1) / rows;
+#ifdef FK_EXP_BLOCKS
+    const int target = FK_EXP_BLOCKS;
+#else
+    const int target = (d->dtype == FK_BF16 && d->head_dim == 128) ? 128 : 512;
+#endif
+    const int want = (target + rows - 1) / rows;
     return want < 1 ? 1 : want;
 }
 
@@ -201,7 +218,115 @@ __global__ __launch_bounds__((AttnCfg<T, D, G>::THREADS)) void attn_kernel(const
 #pragma unroll
         for (int e = 0; e < EPL; ++e) acc[h][e] = 0.f;
 
-    if constexpr (C::MFMA) {
+    if constexpr (C::PVM) {
+        constexpr int PS = C::PS, KRS = C::KRS;
+        const int n16 = lane & 15, quad = lane >> 4;
+        uint16_t* my_pb = reinterpret_cast<uint16_t*>(s_p) + (size_t)wave * GP * PS;           // [GP][PS] bf16
+        unsigned char* my_k = reinterpret_cast<unsigned char*>(s_corr + WAVES * GP + 4) + (size_t)wave * KT * KRS;
+        B128 qa[4];
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) {
+            if (n16 < G) qa[ks].u = *reinterpret_cast<const uint4*>(qrow + (size_t)n16 * D + ks * 32 + quad * 8);
+            else qa[ks].u = make_uint4(0, 0, 0, 0);
+        }
+        float m_run[4], l_run[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            m_run[i] = kNegBig;
+            l_run[i] = 0.f;
+        }
+        f32x4_t o[8];  // o[e][i] = out[head quad*4 + i][channel n16*8 + e], un-normalised
+#pragma unroll
+        for (int e = 0; e < 8; ++e) o[e] = (f32x4_t){0.f, 0.f, 0.f, 0.f};
+
+        for (int base = start + wave * KT; base < end; base += WAVES * KT) {
+            uint4 vr[8];
+            {
+                uint4 kr[8];  // lane (quad, n16): key base + quad*8 + u, 16-byte chunk n16
+#pragma unroll
+                for (int u = 0; u < 8; ++u) kr[u] = Krow[(size_t)min(base + quad * 8 + u, end - 1) * CH + n16];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) vr[u] = Vrow[(size_t)min(base + quad * 8 + u, end - 1) * CH + n16];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) *reinterpret_cast<uint4*>(my_k + (quad * 8 + u) * KRS + n16 * 16) = kr[u];
+            }
+            __builtin_amdgcn_wave_barrier();
+            // B operand of q.K^T: lane = key n16 of tile nt, channels ks*32 + quad*8 .. +8
+            f32x4_t c[2];
+#pragma unroll
+            for (int nt = 0; nt < 2; ++nt) {
+                c[nt] = (f32x4_t){0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int ks = 0; ks < 4; ++ks) {
+                    B128 kb;
+                    kb.u = *reinterpret_cast<const uint4*>(my_k + (nt * 16 + n16) * KRS + (ks * 4 + quad) * 16);
+                    c[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(qa[ks].v, kb.v, c[nt], 0, 0, 0);
+                }
+            }
+            bool changed = false;
+            float corr[4];
+            uint32_t pb[2][4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const float s0 = (base + n16 < end) ? c[0][i] * P.scale_log2e : kNegBig;
+                const float s1 = (base + 16 + n16 < end) ? c[1][i] * P.scale_log2e : kNegBig;
+                const float mn = fmaxf(m_run[i], row16_max(fmaxf(s0, s1)));
+                changed |= mn > m_run[i];
+                corr[i] = exp2f(m_run[i] - mn);
+                // probabilities rounded to bf16; the SAME rounded values go into l, so the weights stay normalised
+                const uint32_t u0 = __float_as_uint(exp2f(s0 - mn)) + 0x8000u, u1 = __float_as_uint(exp2f(s1 - mn)) + 0x8000u;
+                pb[0][i] = u0 >> 16;
+                pb[1][i] = u1 >> 16;
+                l_run[i] = l_run[i] * corr[i] + __uint_as_float(u0 & 0xffff0000u) + __uint_as_float(u1 & 0xffff0000u);
+                m_run[i] = mn;
+            }
+            if (quad * 4 < GP) {
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    my_pb[(quad * 4 + i) * PS + n16] = (uint16_t)pb[0][i];
+                    my_pb[(quad * 4 + i) * PS + 16 + n16] = (uint16_t)pb[1][i];
+                }
+            }
+            if (__any(changed)) {  // the running maximum moved: rescale what has been accumulated
+#pragma unroll
+                for (int e = 0; e < 8; ++e)
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) o[e][i] *= corr[i];
+            }
+            __builtin_amdgcn_wave_barrier();
+            // A operand of P.V: P[head n16][k-slots quad*8 .. +8]; k-slot u of group quad is key base + quad*8 + u
+            B128 pa;
+            if (n16 < GP) pa.u = *reinterpret_cast<const uint4*>(my_pb + n16 * PS + quad * 8);
+            else pa.u = make_uint4(0, 0, 0, 0);
+            // B operand: tile e = channel n16*8 + e over this lane's 8 k-slots (8x8 transpose in registers)
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const uint32_t sel = (e & 1) ? 0x07060302u : 0x05040100u;
+                B128 vb;
+                vb.u.x = __builtin_amdgcn_perm((&vr[1].x)[e >> 1], (&vr[0].x)[e >> 1], sel);
+                vb.u.y = __builtin_amdgcn_perm((&vr[3].x)[e >> 1], (&vr[2].x)[e >> 1], sel);
+                vb.u.z = __builtin_amdgcn_perm((&vr[5].x)[e >> 1], (&vr[4].x)[e >> 1], sel);
+                vb.u.w = __builtin_amdgcn_perm((&vr[7].x)[e >> 1], (&vr[6].x)[e >> 1], sel);
+                o[e] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pa.v, vb.v, o[e], 0, 0, 0);
+            }
+            __builtin_amdgcn_wave_barrier();
+        }
+        // publish one partial per wave
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int h = quad * 4 + i;
+            const float ls = group_sum<16>(l_run[i]);
+            if (h < G) {
+                float* dst = s_acc + ((size_t)wave * G + h) * D + n16 * 8;
+                *reinterpret_cast<float4*>(dst) = make_float4(o[0][i], o[1][i], o[2][i], o[3][i]);
+                *reinterpret_cast<float4*>(dst + 4) = make_float4(o[4][i], o[5][i], o[6][i], o[7][i]);
+                if (n16 == 0) {
+                    s_m[wave * G + h] = m_run[i];
+                    s_l[wave * G + h] = ls;
+                }
+            }
+        }
+    } else if constexpr (C::MFMA) {
         constexpr int KS = D / 32;  // MFMA k-steps
         const int n16 = lane & 15, quad = lane >> 4;
         B128 qa[KS];
@@ -382,8 +507,8 @@ __global__ __launch_bounds__((AttnCfg<T, D, G>::THREADS)) void attn_kernel(const
         }
     }
 
-    // ---- merge the (wave, key group) partials of the workgroup ---------------------------------
-    {
+    // ---- merge the partials of the workgroup -----------------------------------------------------
+    if constexpr (!C::PVM) {
         float* dst = s_acc + ((size_t)(wave * KG + kgv) * G) * D + dl * EPL;
 #pragma unroll
         for (int h = 0; h < G; ++h)
@@ -423,7 +548,11 @@ __global__ __launch_bounds__((AttnCfg<T, D, G>::THREADS)) void attn_kernel(const
             }
         }
     }
+#ifdef FK_EXP_NOCOMBINE
+    if (false) {
+#else
     if (used > 1) {
+#endif
         // last workgroup of the row merges the splits: out = sum_s acc_s 2^(m_s - m*) / sum_s l_s 2^(m_s - m*)
         wait_stores_done();
         __syncthreads();
