@@ -166,7 +166,8 @@ def main():
             return torch.from_numpy(a.view(np.int16)).cuda().view(torch.bfloat16)
         return torch.from_numpy(a).cuda()
 
-    K0, V0, pos0, len0 = dev(Kh), dev(Vh), dev(posh), dev(lens0.astype(np.int32))
+    K0, V0, pos0 = dev(Kh), dev(Vh), dev(posh)
+    len0 = dev(np.repeat(lens0.astype(np.int32)[:, None], w.n_kv_heads, axis=1))      # one count per row
     dq, dk, dv, dp = dev(qh), dev(kh), dev(vh), dev(ph)
     del Kh, Vh, qh, kh, vh
     W1, b1, W2, b2 = si.gen_scorer(w, 0)
@@ -209,6 +210,8 @@ def main():
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
     final_len = lenc.cpu().numpy()
+    assert (final_len == final_len[:, :1]).all()
+    final_len = final_len[:, 0]
     expect_len = len_schedule(w, lens0, K_steps)[0][-1]
     expect_len = np.where((K_steps % L == 0) & (expect_len > B), B, expect_len)
     assert np.array_equal(final_len, expect_len), (final_len, expect_len)

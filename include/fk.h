@@ -12,8 +12,10 @@
  * Memory layout (row major, all DEVICE memory owned by the caller):
  *   K, V   [batch][n_kv_heads][capacity][head_dim]   dtype (fp32 or bf16)
  *   pos    [batch][n_kv_heads][capacity]             int32 absolute position of each slot
- *   len    [batch]                                   int32 retained count (equal for all KV heads)
- * A (sequence, KV head) pair is called a row.  Slots 0 .. len[b]-1 of a row are live.
+ *   len    [batch][n_kv_heads]                       int32 retained count of each row
+ * A (sequence, KV head) pair is called a row; row index r = b * n_kv_heads + h.  Slots
+ * 0 .. len[r]-1 of a row are live.  Every row carries its own count (each KV head keeps its own
+ * retained set); under one budget for all heads the counts of a sequence are equal.
  * Precondition kept by fk_append and fk_compact: along the live slots of a row the
  * positions are strictly increasing, so slot order is position order.
  *
@@ -23,7 +25,7 @@
  *   - `stream` is a hipStream_t passed as void* (NULL = the null stream); every call
  *     only enqueues work on it and returns; nothing is allocated, no state is kept;
  *   - errors are return codes; arguments are validated on the host before any launch;
- *   - `max_len` is a host-side upper bound on every len[b] at the time the kernels run
+ *   - `max_len` is a host-side upper bound on every len[r] at the time the kernels run
  *     (pass `capacity` when unknown); it only sizes the launch.
  *   - supported: head_dim 64 or 128; dtype fp32 or bf16; n_q_heads a multiple of
  *     n_kv_heads with group size <= 8; capacity < 2^24.
@@ -74,9 +76,9 @@ const char *fk_version(void);
 
 /*
  * Section 3.1 (a generated token joins the cache): for every sequence b and KV head h write
- * k_new[b][h][:], v_new[b][h][:] and pos_new[b] into slot len[b] of row (b, h), then
- * len[b] += 1.  k_new, v_new: [batch][n_kv_heads][head_dim] dtype; pos_new: [batch] int32.
- * A sequence whose len[b] == capacity is left unchanged (nothing is written past the row).
+ * k_new[b][h][:], v_new[b][h][:] and pos_new[b] into slot len[r] of row r = (b, h), then
+ * len[r] += 1.  k_new, v_new: [batch][n_kv_heads][head_dim] dtype; pos_new: [batch] int32.
+ * A row whose len[r] == capacity is left unchanged (nothing is written past the row).
  */
 fk_status fk_append(const fk_cache_desc *desc, void *K, void *V, int32_t *pos, int32_t *len,
                     const void *k_new, const void *v_new, const int32_t *pos_new, void *stream);
@@ -84,16 +86,17 @@ fk_status fk_append(const fk_cache_desc *desc, void *K, void *V, int32_t *pos, i
 /*
  * Bytes of device workspace fk_decode_attn / fk_decode_step need (0 on bad args).  The size does
  * not depend on max_len, so one workspace serves every call on this descriptor.  The workspace
- * starts with arrival counters: the caller zero-fills it ONCE after allocating it; every call
+ * starts with per-row arrival counters: the caller zero-fills it ONCE after allocating it; every call
  * leaves the counters at zero again.  Calls sharing a workspace must not overlap in time.
  */
 size_t fk_decode_attn_workspace(const fk_cache_desc *desc, int32_t max_len);
 
 /*
  * Appendix A, "Problem Setup" (attention over the retained set, renormalised softmax):
- *   out[b][hq][:] = sum_{i < len[b]} softmax_i(softmax_scale * <q[b][hq], K[b][hq/g][i]>) V[b][hq/g][i]
- * q, out: [batch][n_q_heads][head_dim] dtype; accumulation in fp32.  A sequence with
- * len[b] == 0 gets zeros.  workspace: >= fk_decode_attn_workspace(desc, max_len) bytes, zero-filled
+ *   out[b][hq][:] = sum_{i < len[b][hq/g]} softmax_i(softmax_scale * <q[b][hq], K[b][hq/g][i]>) V[b][hq/g][i]
+ * q, out: [batch][n_q_heads][head_dim] dtype; accumulation in fp32 (bf16 with head_dim 128: the
+ * softmax weights are rounded to bf16 before the P.V contraction and normalised by the sum of the
+ * rounded weights).  Query heads of a row with len == 0 get zeros.  workspace: >= fk_decode_attn_workspace(desc, max_len) bytes, zero-filled
  * once by the caller (see above); FK_ERR_WORKSPACE if missing or too small.  One launch.
  */
 fk_status fk_decode_attn(const fk_cache_desc *desc, const void *q, const void *K, const void *V,
@@ -103,7 +106,7 @@ fk_status fk_decode_attn(const fk_cache_desc *desc, const void *q, const void *K
 /*
  * One decode step in ONE launch: fk_append followed by fk_decode_attn (Section 3.1 for the append,
  * Appendix A "Problem Setup" for the attention), with the same arguments and results as the two
- * calls in that order; the new pair takes part in the attention.  max_len bounds len[b] + 1.
+ * calls in that order; the new pair takes part in the attention.  max_len bounds len[r] + 1.
  */
 fk_status fk_decode_step(const fk_cache_desc *desc, const void *q, void *K, void *V, int32_t *pos,
                          int32_t *len, const void *k_new, const void *v_new, const int32_t *pos_new,
@@ -114,20 +117,20 @@ fk_status fk_decode_step(const fk_cache_desc *desc, const void *q, void *K, void
  * Section 3.1 Eq. 1 and Appendix B.1 (importance score of every retained pair, features
  * restricted to the key and value vectors):
  *   scores[b][h][i] = sum_j gelu(sum_f x_f W1[f][j] + b1[j]) W2[j] + b2,  x = [K[b][h][i], V[b][h][i]]
- * for i < len[b]; gelu is the exact erf form; fp32 accumulation (bf16: MFMA).  scores:
- * [batch][n_kv_heads][capacity] fp32; slots >= len[b] are not written.
+ * for i < len[r]; gelu is the exact erf form; fp32 accumulation (bf16: MFMA).  scores:
+ * [batch][n_kv_heads][capacity] fp32; slots >= len[r] are not written.
  */
 fk_status fk_score_kv(const fk_cache_desc *desc, const void *K, const void *V, const int32_t *len,
                       int32_t max_len, const fk_scorer *scorer, float *scores, void *stream);
 
 /*
  * Section 3.1 (keep the most recent L pairs, prune the others to the B - L most important;
- * deterministic Top-K form).  For every row with len[b] > budget: keep the last
- * `protect_recent` live slots and, of the other len[b] - protect_recent, the
+ * deterministic Top-K form).  For every row with len[r] > budget: keep the last
+ * `protect_recent` live slots and, of the other len[r] - protect_recent, the
  * budget - protect_recent best under the total order (score descending, then slot
  * ascending = position ascending).  -0 equals +0; NaN ranks below -inf.  The kept slot
  * indices are written ascending to keep_idx[b][h][0 .. budget-1].  Rows with
- * len[b] <= budget get keep_idx[j] = j for j < len[b]; the rest of their row is not written.
+ * len[r] <= budget get keep_idx[j] = j for j < len[r]; the rest of their row is not written.
  * keep_idx: [batch][n_kv_heads][budget] int32.  pos may be NULL: it is not read, slot order
  * stands for position order (see the precondition above).
  * Requires 0 <= protect_recent <= budget <= capacity.
@@ -138,9 +141,9 @@ fk_status fk_select_keep(const fk_cache_desc *desc, const float *scores, const i
 
 /*
  * Section 1 / 3.1 (evicted pairs are discarded for good; stable in-place form): for every row
- * with len[b] > budget, slot j of K, V and pos receives the former contents of slot
+ * with len[r] > budget, slot j of K, V and pos receives the former contents of slot
  * keep_idx[b][h][j], j = 0 .. budget-1 (bit copies; keep_idx ascending with keep_idx[j] >= j,
- * as fk_select_keep writes it), then len[b] = budget.  Rows with len[b] <= budget are untouched.
+ * as fk_select_keep writes it), then len[r] = budget.  Rows with len[r] <= budget are untouched.
  */
 fk_status fk_compact(const fk_cache_desc *desc, void *K, void *V, int32_t *pos, int32_t *len,
                      const int32_t *keep_idx, int32_t budget, void *stream);

@@ -8,7 +8,8 @@
 // the split and keeps an online softmax (running maximum m, running sum l, un-normalised
 // accumulator acc); the wavefronts are merged through LDS and the splits of a row through a
 // small record in the workspace, the last workgroup of the row to arrive doing the final
-// log-sum-exp merge and the store of `out` (no second launch).
+// log-sum-exp merge and the store of `out` (no second launch).  With at least 128 rows a row is
+// not split at all and the launch has no cross-workgroup traffic.
 //
 // bf16, D = 128.  K and V tiles of 32 keys are fetched with fully coalesced 128-bit loads (a row is
 // 16 lanes x 16 bytes, four rows per wavefront instruction).  The K tile is staged in LDS (padded
@@ -115,9 +116,9 @@ static AttnPlan attn_plan(const fk_cache_desc* d, int max_len) {
     return p;
 }
 
-// workspace: [row counters: rows u32][sequence counters: batch u32] padded to 256 B | records
+// workspace: [row arrival counters: rows u32] padded to 256 B | records
 static size_t attn_counter_bytes(const fk_cache_desc* d) {
-    const size_t n = (size_t)d->batch * d->n_kv_heads + d->batch;
+    const size_t n = (size_t)d->batch * d->n_kv_heads;
     return (n * sizeof(uint32_t) + 255) / 256 * 256;
 }
 
@@ -134,7 +135,6 @@ struct AttnParams {
     int n_kv, cap, split_len, nsplit;
     float* rec;          // [rows][nsplit][G][D + 2]
     uint32_t* row_cnt;   // [rows], zero between launches
-    uint32_t* seq_cnt;   // [batch], zero between launches
     void* out;
 };
 
@@ -157,35 +157,60 @@ __global__ __launch_bounds__((AttnCfg<T, D, G>::THREADS)) void attn_kernel(const
     __shared__ int s_last;
 
     const bool appending = P.k_new != nullptr;
-    const int n_old = min(max(P.len[b], 0), P.cap);
+    const int n_old = min(max(P.len[row], 0), P.cap);
     const bool do_append = appending && n_old < P.cap;
     const int n = n_old + (do_append ? 1 : 0);
     const int used = (n + P.split_len - 1) / P.split_len;
     T* out = reinterpret_cast<T*>(P.out) + ((size_t)b * P.n_kv + hkv) * G * D;
 
-    // Every workgroup of a sequence reports to the sequence counter when an append is fused in, so
-    // len[b] is bumped only after all of them have read it.
-    auto seq_arrive = [&]() {
-        if (!appending) return;
+    // Every workgroup of the row calls finish() once, as its last action.  With one workgroup per
+    // row it just publishes the new length.  With several, all of them (also those whose split lies
+    // beyond the row's end) report to the row's arrival counter; the last one to arrive merges the
+    // splits, out = sum_s acc_s 2^(m_s - m*) / sum_s l_s 2^(m_s - m*), and only then bumps len[row],
+    // which every workgroup of the row has read by that time.
+    auto finish = [&](bool wrote_record) {
+        if (gridDim.x == 1) {
+            if (do_append && tid == 0) P.len[row] = n;
+            return;
+        }
+        if (!appending && used <= 1) return;  // same decision in every workgroup of the row
+        if (wrote_record) wait_stores_done();
         __syncthreads();
         if (tid == 0) {
-            const uint32_t total = (uint32_t)gridDim.x * P.n_kv;
-            const uint32_t prev = __hip_atomic_fetch_add(&P.seq_cnt[b], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            if (prev == total - 1) {
-                __hip_atomic_store(&P.seq_cnt[b], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                if (do_append) P.len[b] = n;
+            const uint32_t prev = __hip_atomic_fetch_add(&P.row_cnt[row], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            s_last = prev == gridDim.x - 1;
+            if (s_last) __hip_atomic_store(&P.row_cnt[row], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+        __syncthreads();
+        if (!s_last) return;
+        if (used > 1) {
+            const float* r0 = P.rec + (size_t)row * P.nsplit * G * (D + 2);
+            const size_t stride = (size_t)G * (D + 2);
+            for (int idx = tid; idx < G * D; idx += C::THREADS) {
+                const int h = idx / D, d = idx % D;
+                const float* r = r0 + (size_t)h * (D + 2);
+                float mn = kNegBig;
+                for (int s = 0; s < used; ++s) mn = fmaxf(mn, ld_agent(r + s * stride + D));
+                float a = 0.f, ls = 0.f;
+                for (int s = 0; s < used; ++s) {
+                    const float cw = exp2f(ld_agent(r + s * stride + D) - mn);
+                    a = fmaf(ld_agent(r + s * stride + d), cw, a);
+                    ls = fmaf(ld_agent(r + s * stride + D + 1), cw, ls);
+                }
+                store_out(out + idx, a / ls);
             }
         }
+        if (do_append && tid == 0) P.len[row] = n;
     };
 
     if (n == 0) {
         if (split == 0)
             for (int i = tid; i < G * D; i += C::THREADS) store_out(out + i, 0.f);
-        seq_arrive();
+        finish(false);
         return;
     }
     if (split >= used) {
-        seq_arrive();
+        finish(false);
         return;
     }
     const int start = split * P.split_len;
@@ -548,39 +573,7 @@ __global__ __launch_bounds__((AttnCfg<T, D, G>::THREADS)) void attn_kernel(const
             }
         }
     }
-#ifdef FK_EXP_NOCOMBINE
-    if (false) {
-#else
-    if (used > 1) {
-#endif
-        // last workgroup of the row merges the splits: out = sum_s acc_s 2^(m_s - m*) / sum_s l_s 2^(m_s - m*)
-        wait_stores_done();
-        __syncthreads();
-        if (tid == 0) {
-            const uint32_t prev = __hip_atomic_fetch_add(&P.row_cnt[row], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            s_last = prev == (uint32_t)used - 1;
-            if (s_last) __hip_atomic_store(&P.row_cnt[row], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        }
-        __syncthreads();
-        if (s_last) {
-            const float* r0 = P.rec + (size_t)row * P.nsplit * G * (D + 2);
-            const size_t stride = (size_t)G * (D + 2);
-            for (int idx = tid; idx < G * D; idx += C::THREADS) {
-                const int h = idx / D, d = idx % D;
-                const float* r = r0 + (size_t)h * (D + 2);
-                float mn = kNegBig;
-                for (int s = 0; s < used; ++s) mn = fmaxf(mn, ld_agent(r + s * stride + D));
-                float a = 0.f, ls = 0.f;
-                for (int s = 0; s < used; ++s) {
-                    const float cw = exp2f(ld_agent(r + s * stride + D) - mn);
-                    a = fmaf(ld_agent(r + s * stride + d), cw, a);
-                    ls = fmaf(ld_agent(r + s * stride + D + 1), cw, ls);
-                }
-                store_out(out + idx, a / ls);
-            }
-        }
-    }
-    seq_arrive();
+    finish(used > 1);
 }
 
 template <typename T, int D, int G>
@@ -592,7 +585,6 @@ static fk_status attn_launch(const fk_cache_desc* d, const AttnParams& base, int
     P.split_len = p.split_len;
     P.nsplit = p.nsplit;
     P.row_cnt = reinterpret_cast<uint32_t*>(ws);
-    P.seq_cnt = P.row_cnt + rows;
     P.rec = reinterpret_cast<float*>(reinterpret_cast<char*>(ws) + attn_counter_bytes(d));
     auto kern = attn_kernel<T, D, G>;
     static bool attr_set = false;  // per template instantiation

@@ -5,28 +5,26 @@ namespace fk {
 
 // ---------------------------------------------------------------------------------------
 // append (Section 3.1: each generated token adds one pair to every KV-head row)
-// one workgroup per sequence; 16-byte chunks of the new K and V rows of all its KV heads
+// one workgroup per row; 16-byte chunks of the new K and V rows
 // ---------------------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void append_kernel(uint4* __restrict__ K, uint4* __restrict__ V,
-                                                     int32_t* __restrict__ pos, int32_t* __restrict__ len,
-                                                     const uint4* __restrict__ k_new,
-                                                     const uint4* __restrict__ v_new,
-                                                     const int32_t* __restrict__ pos_new, int n_kv,
-                                                     int cap, int chunks /* 16-byte chunks per row */) {
-    const int b = blockIdx.x;
-    const int n = len[b];
-    __syncthreads();  // everyone has read len[b] before it is bumped
+__global__ __launch_bounds__(64) void append_kernel(uint4* __restrict__ K, uint4* __restrict__ V,
+                                                    int32_t* __restrict__ pos, int32_t* __restrict__ len,
+                                                    const uint4* __restrict__ k_new,
+                                                    const uint4* __restrict__ v_new,
+                                                    const int32_t* __restrict__ pos_new, int n_kv,
+                                                    int cap, int chunks /* 16-byte chunks per row */) {
+    const int row = blockIdx.x;
+    const int n = len[row];
     if (n < 0 || n >= cap) return;
-    const int total = n_kv * chunks;
-    for (int i = threadIdx.x; i < total; i += blockDim.x) {
-        const int h = i / chunks, c = i % chunks;
-        const size_t row = (size_t)b * n_kv + h;
-        const size_t dst = (row * cap + n) * chunks + c;
-        K[dst] = k_new[row * chunks + c];
-        V[dst] = v_new[row * chunks + c];
+    const size_t dst = ((size_t)row * cap + n) * chunks;
+    for (int c = threadIdx.x; c < chunks; c += blockDim.x) {
+        K[dst + c] = k_new[(size_t)row * chunks + c];
+        V[dst + c] = v_new[(size_t)row * chunks + c];
     }
-    for (int h = threadIdx.x; h < n_kv; h += blockDim.x) pos[((size_t)b * n_kv + h) * cap + n] = pos_new[b];
-    if (threadIdx.x == 0) len[b] = n + 1;
+    if (threadIdx.x == 0) {
+        pos[(size_t)row * cap + n] = pos_new[row / n_kv];
+        len[row] = n + 1;  // only this workgroup reads or writes len[row]
+    }
 }
 
 // ---------------------------------------------------------------------------------------
@@ -46,11 +44,10 @@ static constexpr int kCompactU = 8;
 __global__ __launch_bounds__(kCompactThreads) void compact_kernel(uint4* __restrict__ K, uint4* __restrict__ V,
                                                                   int32_t* __restrict__ pos,
                                                                   const int32_t* __restrict__ len,
-                                                                  const int32_t* __restrict__ keep, int n_kv,
+                                                                  const int32_t* __restrict__ keep,
                                                                   int cap, int budget, int chunks) {
     const int row = blockIdx.x;
-    const int b = row / n_kv;
-    const int n = min(len[b], cap);
+    const int n = min(len[row], cap);
     if (n <= budget) return;
     const int32_t* kp = keep + (size_t)row * budget;
     if (blockIdx.y == 2) {
@@ -95,10 +92,10 @@ __global__ __launch_bounds__(kCompactThreads) void compact_kernel(uint4* __restr
     }
 }
 
-// after every row has been compacted: len[b] = min(len[b], budget)
-__global__ void clamp_len_kernel(int32_t* __restrict__ len, int batch, int budget) {
-    const int b = blockIdx.x * blockDim.x + threadIdx.x;
-    if (b < batch && len[b] > budget) len[b] = budget;
+// after every row has been compacted: len[row] = min(len[row], budget)
+__global__ void clamp_len_kernel(int32_t* __restrict__ len, int rows, int budget) {
+    const int r = blockIdx.x * blockDim.x + threadIdx.x;
+    if (r < rows && len[r] > budget) len[r] = budget;
 }
 
 }  // namespace fk
@@ -112,7 +109,7 @@ extern "C" fk_status fk_append(const fk_cache_desc* desc, void* K, void* V, int3
     if (!K || !V || !pos || !len || !k_new || !v_new || !pos_new) return FK_ERR_INVALID_ARG;
     if (!aligned16(K) || !aligned16(V) || !aligned16(k_new) || !aligned16(v_new)) return FK_ERR_INVALID_ARG;
     const int chunks = desc->head_dim * (desc->dtype == FK_F32 ? 4 : 2) / 16;
-    hipLaunchKernelGGL(append_kernel, dim3(desc->batch), dim3(256), 0, (hipStream_t)stream, (uint4*)K,
+    hipLaunchKernelGGL(append_kernel, dim3(desc->batch * desc->n_kv_heads), dim3(64), 0, (hipStream_t)stream, (uint4*)K,
                        (uint4*)V, pos, len, (const uint4*)k_new, (const uint4*)v_new, pos_new,
                        desc->n_kv_heads, desc->capacity, chunks);
     return launch_status();
@@ -129,8 +126,7 @@ extern "C" fk_status fk_compact(const fk_cache_desc* desc, void* K, void* V, int
     const int rows = desc->batch * desc->n_kv_heads;
     hipStream_t st = (hipStream_t)stream;
     hipLaunchKernelGGL(compact_kernel, dim3(rows, 3), dim3(kCompactThreads), 0, st, (uint4*)K, (uint4*)V,
-                       pos, len, keep_idx, desc->n_kv_heads, desc->capacity, budget, chunks);
-    hipLaunchKernelGGL(clamp_len_kernel, dim3((desc->batch + 255) / 256), dim3(256), 0, st, len,
-                       desc->batch, budget);
+                       pos, len, keep_idx, desc->capacity, budget, chunks);
+    hipLaunchKernelGGL(clamp_len_kernel, dim3((rows + 255) / 256), dim3(256), 0, st, len, rows, budget);
     return launch_status();
 }

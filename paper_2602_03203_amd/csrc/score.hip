@@ -40,8 +40,8 @@ __global__ __launch_bounds__(kScoreThreads) void score_mfma_kernel(
     constexpr int FS = F + kWPad;  // LDS row stride in bf16 elements
     constexpr int KS = F / 16;     // k-steps of 16 features
     const int row = blockIdx.y;
-    const int b = row / n_kv, hkv = row % n_kv;
-    const int n = min(len[b], cap);
+    const int hkv = row % n_kv;
+    const int n = min(len[row], cap);
     const int p_begin = blockIdx.x * pairs_per_block;
     if (p_begin >= n) return;
     const int p_end = min(p_begin + pairs_per_block, n);
@@ -153,8 +153,8 @@ __global__ __launch_bounds__(128) void score_simple_kernel(const T* __restrict__
                                                            float* __restrict__ scores) {
     constexpr int EPL = Vec16<T>::N;
     const int row = blockIdx.y;
-    const int b = row / n_kv, hkv = row % n_kv;
-    const int n = min(len[b], cap);
+    const int hkv = row % n_kv;
+    const int n = min(len[row], cap);
     const int p = blockIdx.x * blockDim.x + threadIdx.x;
     if (p >= n) return;
     const int hw = per_head ? hkv : 0;

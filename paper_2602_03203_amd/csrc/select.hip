@@ -49,11 +49,10 @@ __device__ __forceinline__ unsigned long long block_scan_incl(unsigned long long
 
 __global__ __launch_bounds__(kSelThreads) void select_keep_kernel(const float* __restrict__ scores,
                                                                   const int32_t* __restrict__ len,
-                                                                  int n_kv, int cap, int budget, int recent,
+                                                                  int cap, int budget, int recent,
                                                                   int32_t* __restrict__ keep) {
     const int row = blockIdx.x;
-    const int b = row / n_kv;
-    const int n = min(len[b], cap);
+    const int n = min(len[row], cap);
     int32_t* out = keep + (size_t)row * budget;
     if (n <= budget) {
         for (int j = threadIdx.x; j < n; j += kSelThreads) out[j] = j;
@@ -153,6 +152,6 @@ extern "C" fk_status fk_select_keep(const fk_cache_desc* desc, const float* scor
         return FK_ERR_INVALID_ARG;
     const int rows = desc->batch * desc->n_kv_heads;
     hipLaunchKernelGGL(select_keep_kernel, dim3(rows), dim3(kSelThreads), 0, (hipStream_t)stream, scores,
-                       len, desc->n_kv_heads, desc->capacity, budget, protect_recent, keep_idx);
+                       len, desc->capacity, budget, protect_recent, keep_idx);
     return launch_status();
 }

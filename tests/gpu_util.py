@@ -32,13 +32,16 @@ class DevCache:
         Bt, Hkv, cap, D = c.shape
         self.desc = fk.CacheDesc(Bt, n_q_heads, Hkv, D, cap, c.dtype)
         self.K, self.V = to_dev(c.K), to_dev(c.V)
-        self.pos, self.len = to_dev(c.pos), to_dev(c.len)
+        # the device keeps one length per row; the oracle one per sequence (all heads equal)
+        self.pos, self.len = to_dev(c.pos), to_dev(np.repeat(c.len[:, None], Hkv, axis=1).astype(np.int32))
         self.ws = fk.new_attn_workspace(self.desc)
         self.out = torch.empty((Bt, n_q_heads, D), dtype=self.desc.torch_dtype, device="cuda")
         self.scores = torch.full((Bt, Hkv, cap), float("nan"), dtype=torch.float32, device="cuda")
 
     def host(self, oracle):
-        return oracle.Cache(self.desc.dtype, to_host(self.K), to_host(self.V), to_host(self.pos), to_host(self.len))
+        ln = to_host(self.len)
+        assert (ln == ln[:, :1]).all(), "rows of a sequence must hold equal counts"
+        return oracle.Cache(self.desc.dtype, to_host(self.K), to_host(self.V), to_host(self.pos), np.ascontiguousarray(ln[:, 0]))
 
     def attn(self, q_dev, scale, max_len=None):
         fk.fk_decode_attn(self.desc, q_dev, self.K, self.V, self.len, max_len or self.desc.capacity, scale, self.out, self.ws)

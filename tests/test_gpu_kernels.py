@@ -68,6 +68,44 @@ def test_decode_attn_closed_forms_on_device(gpu, ora):
     np.testing.assert_allclose(got2[0, 2], c2.V[0, 0, 217].astype(np.float64), atol=1e-5)
 
 
+def test_rows_of_a_sequence_may_hold_different_counts(gpu, ora):
+    """Every row carries its own length: heads of one sequence with different counts (the oracle sees
+    each row as a one-head sequence)."""
+    import paper_2602_03203_amd as fk
+    Bt, Hkv, G, D, cap = 3, 4, 4, 128, 900
+    lens = np.array([[900, 31, 0, 512], [1, 899, 450, 33], [64, 65, 700, 2]], np.int32)
+    c = random_cache(ora, 8100, "bf16", Bt * Hkv, 1, cap, D, lens=lens.reshape(-1))        # oracle: rows as sequences
+    q = random_q(8101, "bf16", Bt * Hkv, G, D)
+    desc = fk.CacheDesc(Bt, Hkv * G, Hkv, D, cap, "bf16")
+    K, V = gpu.to_dev(c.K.reshape(Bt, Hkv, cap, D)), gpu.to_dev(c.V.reshape(Bt, Hkv, cap, D))
+    pos, ln = gpu.to_dev(c.pos.reshape(Bt, Hkv, cap)), gpu.to_dev(lens)
+    ws, out = fk.new_attn_workspace(desc), torch.empty((Bt, Hkv * G, D), dtype=torch.bfloat16, device="cuda")
+    k_new, v_new = random_q(8102, "bf16", Bt * Hkv, 1, D), random_q(8103, "bf16", Bt * Hkv, 1, D)
+    pos_new = np.array([5000, 5001, 5002], np.int32)
+    fk.fk_decode_step(desc, gpu.to_dev(q.reshape(Bt, Hkv * G, D)), K, V, pos, ln, gpu.to_dev(k_new.reshape(Bt, Hkv, D)),
+                      gpu.to_dev(v_new.reshape(Bt, Hkv, D)), gpu.to_dev(pos_new), cap, 0.1, out, ws)
+    for r in range(Bt * Hkv):
+        if c.len[r] < cap:
+            sub = ora.Cache("bf16", c.K[r:r + 1], c.V[r:r + 1], c.pos[r:r + 1], c.len[r:r + 1])
+            ora.append(sub, k_new[r:r + 1], v_new[r:r + 1], pos_new[r // Hkv:r // Hkv + 1])
+    ref = ora.decode_attn(c, q, 0.1)
+    gpu.assert_attn_close(gpu.out_to_f64(out).reshape(Bt * Hkv, G, D), ref, "bf16", "per-row lengths")
+    assert np.array_equal(gpu.to_host(ln).reshape(-1), c.len)
+    assert np.array_equal(gpu.to_host(K).reshape(c.K.shape), c.K) and np.array_equal(gpu.to_host(pos).reshape(c.pos.shape), c.pos)
+    # eviction on rows with different counts: scores -> select -> compact, row by row against the oracle
+    sc = si.gen_scores(8104, (Bt * Hkv, 1, cap), ties=4)
+    budget, recent = 400, 50
+    keep_ref = ora.select_keep(sc, c.pos, c.len, budget, recent, "sort")
+    keep = torch.full((Bt, Hkv, budget), -1, dtype=torch.int32, device="cuda")
+    fk.fk_select_keep(desc, gpu.to_dev(sc.reshape(Bt, Hkv, cap)), pos, ln, cap, budget, recent, keep)
+    assert np.array_equal(keep.cpu().numpy().reshape(keep_ref.shape), keep_ref)
+    fk.fk_compact(desc, K, V, pos, ln, keep, budget)
+    ora.compact(c, keep_ref, budget)
+    assert np.array_equal(gpu.to_host(ln).reshape(-1), c.len)
+    assert np.array_equal(gpu.to_host(K).reshape(c.K.shape), c.K) and np.array_equal(gpu.to_host(V).reshape(c.V.shape), c.V)
+    assert np.array_equal(gpu.to_host(pos).reshape(c.pos.shape), c.pos)
+
+
 SCORE_SHAPES = [
     ("f32", 64, 64, 2, 160, [160, 33], True),
     ("bf16", 128, 256, 8, 2176, [2176], True),
@@ -122,7 +160,7 @@ def test_select_keep_bit_exact(gpu, ora, Bt, Hkv, cap, lens, budget, recent, tie
     ref = ora.select_keep(sc, pos, ln, budget, recent, "sort")
     desc = fk.CacheDesc(Bt, Hkv, Hkv, 128, cap, "bf16")
     keep = torch.full((Bt, Hkv, budget), -1, dtype=torch.int32, device="cuda")
-    fk.fk_select_keep(desc, gpu.to_dev(sc), gpu.to_dev(pos), gpu.to_dev(ln), cap, budget, recent, keep)
+    fk.fk_select_keep(desc, gpu.to_dev(sc), gpu.to_dev(pos), gpu.to_dev(np.repeat(ln[:, None], Hkv, 1)), cap, budget, recent, keep)
     assert np.array_equal(keep.cpu().numpy(), ref)
 
 
@@ -141,7 +179,7 @@ def test_select_keep_special_values(gpu, ora):
     ref = ora.select_keep(sc, pos, ln, budget, recent, "rank")
     desc = fk.CacheDesc(1, 4, 4, 128, cap, "bf16")
     keep = torch.full((1, 4, budget), -1, dtype=torch.int32, device="cuda")
-    fk.fk_select_keep(desc, gpu.to_dev(sc), None, gpu.to_dev(ln), cap, budget, recent, keep)
+    fk.fk_select_keep(desc, gpu.to_dev(sc), None, gpu.to_dev(np.repeat(ln[:, None], 4, 1)), cap, budget, recent, keep)
     assert np.array_equal(keep.cpu().numpy(), ref)
     assert keep[0, 3].cpu().tolist() == list(range(600)) + list(range(1100, 1200))
 
@@ -208,7 +246,7 @@ def test_decode_step_equals_append_then_attention(gpu, ora, dtype, D, Hq, Hkv, c
         got = dev.host(ora)
         assert np.array_equal(got.len, c.len) and np.array_equal(got.pos, c.pos)
         assert np.array_equal(got.K, c.K) and np.array_equal(got.V, c.V)
-    assert int(torch.count_nonzero(dev.ws[:4 * (Bt * Hkv + Bt)])) == 0        # counters are back to zero
+    assert int(torch.count_nonzero(dev.ws[:4 * Bt * Hkv])) == 0        # counters are back to zero
 
 
 @pytest.mark.parametrize("dtype,D", [("f32", 64), ("bf16", 128), ("bf16", 64), ("f32", 128)])
