@@ -218,19 +218,22 @@ __global__ __launch_bounds__((AttnCfg<T, D, G>::THREADS)) void attn_kernel(const
 
     T* Kr = reinterpret_cast<T*>(P.K) + (size_t)row * P.cap * D;
     T* Vr = reinterpret_cast<T*>(P.V) + (size_t)row * P.cap * D;
-    if (do_append && n_old >= start && n_old < end) {
-        // this workgroup owns the slot of the new pair: write it, then read it back like any other
+    // The workgroup whose split holds the slot of the new pair stores it into the cache.  The bf16
+    // D = 128 path never waits for that store: lanes that need the new row read it from k_new / v_new.
+    const bool owns_new = do_append && n_old >= start && n_old < end;
+    const uint4* knew_row = reinterpret_cast<const uint4*>(reinterpret_cast<const T*>(P.k_new) + (size_t)row * D);
+    const uint4* vnew_row = reinterpret_cast<const uint4*>(reinterpret_cast<const T*>(P.v_new) + (size_t)row * D);
+    if (owns_new) {
         if (tid < CH) {
-            reinterpret_cast<uint4*>(Kr + (size_t)n_old * D)[tid] =
-                reinterpret_cast<const uint4*>(reinterpret_cast<const T*>(P.k_new) + (size_t)row * D)[tid];
+            reinterpret_cast<uint4*>(Kr + (size_t)n_old * D)[tid] = knew_row[tid];
         } else if (tid < 2 * CH) {
-            reinterpret_cast<uint4*>(Vr + (size_t)n_old * D)[tid - CH] =
-                reinterpret_cast<const uint4*>(reinterpret_cast<const T*>(P.v_new) + (size_t)row * D)[tid - CH];
+            reinterpret_cast<uint4*>(Vr + (size_t)n_old * D)[tid - CH] = vnew_row[tid - CH];
         } else if (tid == 2 * CH) {
             P.pos[(size_t)row * P.cap + n_old] = P.pos_new[b];
         }
-        __syncthreads();
+        if constexpr (!C::PVM) __syncthreads();  // the other paths read the row back from the cache
     }
+    const int new_slot = owns_new ? n_old : -1;
     const uint4* Krow = reinterpret_cast<const uint4*>(Kr);
     const uint4* Vrow = reinterpret_cast<const uint4*>(Vr);
     const T* qrow = reinterpret_cast<const T*>(P.q) + ((size_t)b * P.n_kv + hkv) * G * D;
@@ -269,9 +272,15 @@ __global__ __launch_bounds__((AttnCfg<T, D, G>::THREADS)) void attn_kernel(const
             {
                 uint4 kr[8];  // lane (quad, n16): key base + quad*8 + u, 16-byte chunk n16
 #pragma unroll
-                for (int u = 0; u < 8; ++u) kr[u] = Krow[(size_t)min(base + quad * 8 + u, end - 1) * CH + n16];
+                for (int u = 0; u < 8; ++u) {
+                    const int kc = min(base + quad * 8 + u, end - 1);
+                    kr[u] = (kc == new_slot ? knew_row : Krow + (size_t)kc * CH)[n16];
+                }
 #pragma unroll
-                for (int u = 0; u < 8; ++u) vr[u] = Vrow[(size_t)min(base + quad * 8 + u, end - 1) * CH + n16];
+                for (int u = 0; u < 8; ++u) {
+                    const int kc = min(base + quad * 8 + u, end - 1);
+                    vr[u] = (kc == new_slot ? vnew_row : Vrow + (size_t)kc * CH)[n16];
+                }
 #pragma unroll
                 for (int u = 0; u < 8; ++u) *reinterpret_cast<uint4*>(my_k + (quad * 8 + u) * KRS + n16 * 16) = kr[u];
             }
