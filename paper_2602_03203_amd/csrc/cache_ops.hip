@@ -30,16 +30,28 @@ __global__ __launch_bounds__(64) void append_kernel(uint4* __restrict__ K, uint4
 // ---------------------------------------------------------------------------------------
 // compact (stable in-place gather)
 //
-// keep[] is ascending with keep[j] >= j.  Destination slots are processed in ascending
-// tiles of TILE slots by ONE workgroup per (row, tensor): all sources of a tile are loaded
-// into registers, a barrier, then the tile is stored.  A store of tile t lands in slots
+// keep[] is ascending with keep[j] >= j.  A workgroup owns one 32-byte column slice of one
+// tensor of one row (bytes of different slices never alias, so slices are independent) and
+// walks the destination slots in ascending tiles of 2048 slots (budgets up to 2048: one tile,
+// i.e. the whole slice is read, then written): all sources of a tile are loaded into
+// registers, a barrier, then the tile is stored.  A store of tile t lands in slots
 // [tT, (t+1)T); a source of any later tile is >= (t+1)T, and every source of tile t or of an
 // earlier tile has already been read, so no live source is overwritten.  Entries with
 // keep[j] == j (the untouched prefix) cost no traffic.
-// grid.x = row, grid.y = 0: K, 1: V, 2: pos
+// grid.x = row, grid.y = tensor * slices + slice (K slices, then V slices), last y = pos
 // ---------------------------------------------------------------------------------------
-static constexpr int kCompactThreads = 256;
-static constexpr int kCompactU = 8;
+#ifndef FK_COMPACT_THREADS
+#define FK_COMPACT_THREADS 1024
+#endif
+static constexpr int kCompactThreads = FK_COMPACT_THREADS;
+#ifndef FK_COMPACT_U
+#define FK_COMPACT_U 4
+#endif
+#ifndef FK_COMPACT_SLICE
+#define FK_COMPACT_SLICE 2
+#endif
+static constexpr int kCompactU = FK_COMPACT_U;
+static constexpr int kSliceChunks = FK_COMPACT_SLICE;  // 16-byte chunks per column slice
 
 __global__ __launch_bounds__(kCompactThreads) void compact_kernel(uint4* __restrict__ K, uint4* __restrict__ V,
                                                                   int32_t* __restrict__ pos,
@@ -50,7 +62,8 @@ __global__ __launch_bounds__(kCompactThreads) void compact_kernel(uint4* __restr
     const int n = min(len[row], cap);
     if (n <= budget) return;
     const int32_t* kp = keep + (size_t)row * budget;
-    if (blockIdx.y == 2) {
+    const int slices = chunks / kSliceChunks;
+    if ((int)blockIdx.y == 2 * slices) {
         int32_t* p = pos + (size_t)row * cap;
         for (int base = 0; base < budget; base += kCompactThreads * kCompactU) {
             int32_t val[kCompactU];
@@ -70,10 +83,11 @@ __global__ __launch_bounds__(kCompactThreads) void compact_kernel(uint4* __restr
         }
         return;
     }
-    uint4* X = (blockIdx.y == 0 ? K : V) + (size_t)row * cap * chunks;
-    const int spi = kCompactThreads / chunks;  // slots per load instruction of the workgroup
-    const int sl = threadIdx.x / chunks;       // slot within that group
-    const int c = threadIdx.x % chunks;        // 16-byte chunk of the row
+    const int tensor = blockIdx.y / slices, slice = blockIdx.y % slices;
+    uint4* X = (tensor == 0 ? K : V) + (size_t)row * cap * chunks + slice * kSliceChunks;
+    constexpr int spi = kCompactThreads / kSliceChunks;  // slots per load instruction of the workgroup
+    const int sl = threadIdx.x / kSliceChunks;           // slot within that group
+    const int c = threadIdx.x % kSliceChunks;            // 16-byte chunk inside the slice
     for (int base = 0; base < budget; base += spi * kCompactU) {
         uint4 val[kCompactU];
         int src[kCompactU];
@@ -81,13 +95,21 @@ __global__ __launch_bounds__(kCompactThreads) void compact_kernel(uint4* __restr
         for (int u = 0; u < kCompactU; ++u) {
             const int j = base + u * spi + sl;
             src[u] = j < budget ? kp[j] : -1;
+#ifdef FK_EXP_NOLOAD
+            val[u] = make_uint4(src[u], j, 0, 0);
+#else
             if (src[u] >= 0 && src[u] < n && src[u] != j) val[u] = X[(size_t)src[u] * chunks + c];
+#endif
         }
         __syncthreads();
 #pragma unroll
         for (int u = 0; u < kCompactU; ++u) {
             const int j = base + u * spi + sl;
+#ifdef FK_EXP_NOSTORE
+            if (src[u] >= 0 && src[u] < n && src[u] != j && val[u].x == 0x12345u) X[(size_t)j * chunks + c] = val[u];
+#else
             if (src[u] >= 0 && src[u] < n && src[u] != j) X[(size_t)j * chunks + c] = val[u];
+#endif
         }
     }
 }
@@ -125,7 +147,7 @@ extern "C" fk_status fk_compact(const fk_cache_desc* desc, void* K, void* V, int
     const int chunks = desc->head_dim * (desc->dtype == FK_F32 ? 4 : 2) / 16;
     const int rows = desc->batch * desc->n_kv_heads;
     hipStream_t st = (hipStream_t)stream;
-    hipLaunchKernelGGL(compact_kernel, dim3(rows, 3), dim3(kCompactThreads), 0, st, (uint4*)K, (uint4*)V,
+    hipLaunchKernelGGL(compact_kernel, dim3(rows, 2 * (chunks / kSliceChunks) + 1), dim3(kCompactThreads), 0, st, (uint4*)K, (uint4*)V,
                        pos, len, keep_idx, desc->capacity, budget, chunks);
     hipLaunchKernelGGL(clamp_len_kernel, dim3((rows + 255) / 256), dim3(256), 0, st, len, rows, budget);
     return launch_status();
