@@ -93,6 +93,22 @@ def len_schedule(w: si.Workload, lens0: np.ndarray, n_steps: int):
     return out, ev
 
 
+def measured_traffic(w: si.Workload, steps: int):
+    """HBM bytes per attention launch from the committed rocprofv3 counter summary (FETCH_SIZE and
+    WRITE_SIZE runs of this same command, each scaled on a plain copy of known size); None when the
+    summary does not cover this workload / step count."""
+    if w.name != "cfg1-qwen3-4b-layer" or steps != w.steps:
+        return None
+    path = os.path.join(ROOT, "profiles", "attn_kernel_cfg1_hbm_traffic.txt")
+    try:
+        for line in open(path):
+            if line.startswith("traffic_bytes_per_launch"):
+                return float(line.split("=")[1])
+    except OSError:
+        pass
+    return None
+
+
 def attn_bytes(w: si.Workload, lens_row: np.ndarray) -> float:
     """Algorithmic bytes of one attention launch: K and V once per KV head, plus q and out."""
     e = w.elem_bytes
@@ -243,7 +259,8 @@ def main():
         avg_bytes = total_attn_bytes / K_steps
         achieved = avg_bytes / (ms.mean() * 1e-3) / 1e9
         result["roofline"] = {"kernel": "attn_kernel (fk_decode_step: append + split-K attention + merge, one launch)", "bound": "hbm", "achieved": achieved,
-                              "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                              "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
+                              "traffic": measured_traffic(w, K_steps),
                               "avg_launch_us": float(ms.mean() * 1e3), "algorithmic_bytes_per_launch": avg_bytes}
     if not args.no_cpu:
         result["cpu_baseline"] = cpu_baseline(w, host_threads)
