@@ -150,6 +150,7 @@ def main():
     ap.add_argument("--steps", type=int, default=None, help="timed decode steps (default: the workload's)")
     ap.add_argument("--warmup", type=int, default=256)
     ap.add_argument("--config", type=int, default=1)
+    ap.add_argument("--prompt", type=int, default=None, help="override the prompt length (to start near the steady state)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--no-kernel-timing", action="store_true", help="skip the HIP-event pass over the attention launches")
     args = ap.parse_args()
@@ -164,8 +165,10 @@ def main():
     host_threads = min(16, os.cpu_count() or 1)
 
     w = si.config(args.config)
-    if w.layers != 1:
-        sys.exit("bench.py times single-layer workloads (configs 0, 1, 4)")
+    if w.layers != 1:   # stacks: every layer runs the same kernels on its own cache; one layer is timed
+        w = w.scaled(name=f"{w.name} (one layer of {w.layers})", layers=1)
+    if args.prompt is not None:
+        w = w.scaled(name=f"{w.name} (prompt {args.prompt})", prompt=args.prompt)
     K_steps = args.steps if args.steps is not None else w.steps
     W_steps = args.warmup
     n_gen = max(K_steps, W_steps)

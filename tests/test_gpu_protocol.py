@@ -134,3 +134,23 @@ def test_gqa7_mixture_sampled_rows(gpu, ora):
     w = si.config(3).scaled(layers=1, batch=4, prompt=4096 - 64)
     rows = [(0, 0), (3, 2)]
     assert lockstep(gpu, ora, w, 200, sample_rows=rows, scale=128.0 ** 0.5, check_every=16) >= 2
+
+
+def test_long_budget_shape_sampled_rows(gpu, ora):
+    """configs[2] row shape (32/8 heads, D 128, B 16384, L 128, capacity 16512), two sequences of one
+    layer: rows are split across workgroups (few rows) and compaction / selection run several tiles."""
+    w = si.config(2).scaled(layers=1, batch=2, prompt=16384 - 128)
+    rows = [(0, 1), (1, 6)]
+    assert lockstep(gpu, ora, w, 300, sample_rows=rows, scale=128.0 ** 0.5, check_every=32) >= 2
+
+
+def test_ragged_batch_shape_sampled_rows(gpu, ora):
+    """configs[4] shape (ragged lengths up to 32768, B 8192, L 128, capacity 32896), four sequences: the
+    first event prunes rows far over budget in one go, rows under budget are left alone."""
+    w = si.config(4).scaled(batch=4)
+    lens0 = si.initial_lengths(w)
+    assert lens0.max() > w.budget + w.interval and len(set(lens0.tolist())) == 4
+    b_long = int(np.argmax(lens0))
+    b_short = int(np.argmin(lens0))
+    rows = [(b_long, 0), (b_short, 5)]
+    assert lockstep(gpu, ora, w, 260, sample_rows=rows, scale=128.0 ** 0.5, check_every=32) >= 2
