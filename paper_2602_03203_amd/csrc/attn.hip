@@ -50,6 +50,9 @@ __device__ __forceinline__ void wait_stores_done() {
     __builtin_amdgcn_s_waitcnt(0x0F70);
 }
 
+// i-th dword of a 16-byte register quad; i is a compile-time constant after unrolling
+__device__ __forceinline__ uint32_t dword_of(const uint4& v, int i) { return i == 0 ? v.x : (i == 1 ? v.y : (i == 2 ? v.z : v.w)); }
+
 template <int CTRL>
 __device__ __forceinline__ float dpp_max_step(float v) { return fmaxf(v, dpp_f<CTRL>(v)); }
 __device__ __forceinline__ float row16_max(float v) {
@@ -92,11 +95,7 @@ struct AttnPlan {
 // cross-workgroup merge at the end of the launch); the other kernels want about two per CU.
 static int attn_max_splits(const fk_cache_desc* d) {
     const int rows = d->batch * d->n_kv_heads;
-#ifdef FK_EXP_BLOCKS
-    const int target = FK_EXP_BLOCKS;
-#else
     const int target = (d->dtype == FK_BF16 && d->head_dim == 128) ? 128 : 512;
-#endif
     const int want = (target + rows - 1) / rows;
     return want < 1 ? 1 : want;
 }
@@ -337,10 +336,10 @@ __global__ __launch_bounds__((AttnCfg<T, D, G>::THREADS)) void attn_kernel(const
             for (int e = 0; e < 8; ++e) {
                 const uint32_t sel = (e & 1) ? 0x07060302u : 0x05040100u;
                 B128 vb;
-                vb.u.x = __builtin_amdgcn_perm((&vr[1].x)[e >> 1], (&vr[0].x)[e >> 1], sel);
-                vb.u.y = __builtin_amdgcn_perm((&vr[3].x)[e >> 1], (&vr[2].x)[e >> 1], sel);
-                vb.u.z = __builtin_amdgcn_perm((&vr[5].x)[e >> 1], (&vr[4].x)[e >> 1], sel);
-                vb.u.w = __builtin_amdgcn_perm((&vr[7].x)[e >> 1], (&vr[6].x)[e >> 1], sel);
+                vb.u.x = __builtin_amdgcn_perm(dword_of(vr[1], e >> 1), dword_of(vr[0], e >> 1), sel);
+                vb.u.y = __builtin_amdgcn_perm(dword_of(vr[3], e >> 1), dword_of(vr[2], e >> 1), sel);
+                vb.u.z = __builtin_amdgcn_perm(dword_of(vr[5], e >> 1), dword_of(vr[4], e >> 1), sel);
+                vb.u.w = __builtin_amdgcn_perm(dword_of(vr[7], e >> 1), dword_of(vr[6], e >> 1), sel);
                 o[e] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pa.v, vb.v, o[e], 0, 0, 0);
             }
             __builtin_amdgcn_wave_barrier();

@@ -40,18 +40,9 @@ __global__ __launch_bounds__(64) void append_kernel(uint4* __restrict__ K, uint4
 // keep[j] == j (the untouched prefix) cost no traffic.
 // grid.x = row, grid.y = tensor * slices + slice (K slices, then V slices), last y = pos
 // ---------------------------------------------------------------------------------------
-#ifndef FK_COMPACT_THREADS
-#define FK_COMPACT_THREADS 1024
-#endif
-static constexpr int kCompactThreads = FK_COMPACT_THREADS;
-#ifndef FK_COMPACT_U
-#define FK_COMPACT_U 4
-#endif
-#ifndef FK_COMPACT_SLICE
-#define FK_COMPACT_SLICE 2
-#endif
-static constexpr int kCompactU = FK_COMPACT_U;
-static constexpr int kSliceChunks = FK_COMPACT_SLICE;  // 16-byte chunks per column slice
+static constexpr int kCompactThreads = 1024;
+static constexpr int kCompactU = 4;     // 16-byte loads in flight per thread
+static constexpr int kSliceChunks = 2;  // 16-byte chunks per column slice
 
 __global__ __launch_bounds__(kCompactThreads) void compact_kernel(uint4* __restrict__ K, uint4* __restrict__ V,
                                                                   int32_t* __restrict__ pos,
@@ -95,21 +86,13 @@ __global__ __launch_bounds__(kCompactThreads) void compact_kernel(uint4* __restr
         for (int u = 0; u < kCompactU; ++u) {
             const int j = base + u * spi + sl;
             src[u] = j < budget ? kp[j] : -1;
-#ifdef FK_EXP_NOLOAD
-            val[u] = make_uint4(src[u], j, 0, 0);
-#else
             if (src[u] >= 0 && src[u] < n && src[u] != j) val[u] = X[(size_t)src[u] * chunks + c];
-#endif
         }
         __syncthreads();
 #pragma unroll
         for (int u = 0; u < kCompactU; ++u) {
             const int j = base + u * spi + sl;
-#ifdef FK_EXP_NOSTORE
-            if (src[u] >= 0 && src[u] < n && src[u] != j && val[u].x == 0x12345u) X[(size_t)j * chunks + c] = val[u];
-#else
             if (src[u] >= 0 && src[u] < n && src[u] != j) X[(size_t)j * chunks + c] = val[u];
-#endif
         }
     }
 }
