@@ -265,6 +265,24 @@ def main():
                               "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
                               "traffic": measured_traffic(w, K_steps),
                               "avg_launch_us": float(ms.mean() * 1e3), "algorithmic_bytes_per_launch": avg_bytes}
+    if "roofline" in result:
+        # achievable streaming-read bandwidth on this machine, beside the nominal peak: the K cache of this
+        # workload (fits the Infinity Cache at the default shape) and a 4 GiB buffer (HBM resident)
+        sink = torch.zeros(4, dtype=torch.int32, device="cuda")
+        big = torch.empty(1 << 30, dtype=torch.int32, device="cuda")
+        big.fill_(1)
+        def stream_gbs(t, iters):
+            for _ in range(3):
+                fk.fk_stream_read(t, sink, stream)
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(stream)
+            for _ in range(iters):
+                fk.fk_stream_read(t, sink, stream)
+            e1.record(stream)
+            torch.cuda.synchronize()
+            return t.numel() * t.element_size() * iters / (e0.elapsed_time(e1) * 1e-3) / 1e9
+        result["roofline"]["stream_read_gbs"] = {"k_cache": stream_gbs(Kc, 50), "buffer_4gib": stream_gbs(big, 10)}
+        del big
     if not args.no_cpu:
         result["cpu_baseline"] = cpu_baseline(w, host_threads)
     print(json.dumps(result), flush=True)

@@ -148,6 +148,13 @@ fk_status fk_select_keep(const fk_cache_desc *desc, const float *scores, const i
 fk_status fk_compact(const fk_cache_desc *desc, void *K, void *V, int32_t *pos, int32_t *len,
                      const int32_t *keep_idx, int32_t budget, void *stream);
 
+/*
+ * Measurement helper, not part of the method: reads `bytes` (>= 16) of device memory at `src` with
+ * 16-byte loads and discards them; `sink` is 4 bytes of device memory.  bench.py times it to report
+ * the achievable streaming bandwidth of the box beside the nominal HBM peak.
+ */
+fk_status fk_stream_read(const void *src, size_t bytes, void *sink, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

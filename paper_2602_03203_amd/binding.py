@@ -20,7 +20,7 @@ FK_OK, FK_ERR_INVALID_ARG, FK_ERR_UNSUPPORTED, FK_ERR_WORKSPACE, FK_ERR_LAUNCH =
 FK_F32, FK_BF16 = 0, 1
 
 SYMBOLS = ["fk_status_string", "fk_version", "fk_append", "fk_decode_attn_workspace", "fk_decode_attn", "fk_decode_step",
-           "fk_score_kv", "fk_select_keep", "fk_compact"]
+           "fk_score_kv", "fk_select_keep", "fk_compact", "fk_stream_read"]
 
 
 class fk_cache_desc(ctypes.Structure):
@@ -60,6 +60,7 @@ def lib() -> ctypes.CDLL:
         L.fk_score_kv.restype, L.fk_score_kv.argtypes = ctypes.c_int, [dp, vp, vp, vp, i32, sp, vp, vp]
         L.fk_select_keep.restype, L.fk_select_keep.argtypes = ctypes.c_int, [dp, vp, vp, vp, i32, i32, i32, vp, vp]
         L.fk_compact.restype, L.fk_compact.argtypes = ctypes.c_int, [dp, vp, vp, vp, vp, vp, i32, vp]
+        L.fk_stream_read.restype, L.fk_stream_read.argtypes = ctypes.c_int, [vp, sz, vp, vp]
         _lib = L
     return _lib
 
@@ -155,3 +156,8 @@ def fk_select_keep(desc: CacheDesc, scores, pos, length, max_len: int, budget: i
 def fk_compact(desc: CacheDesc, K, V, pos, length, keep_idx, budget: int, stream=None) -> None:
     _check(lib().fk_compact(ctypes.byref(desc.c()), _ptr(K), _ptr(V), _ptr(pos), _ptr(length), _ptr(keep_idx),
                             int(budget), _stream(stream)), "fk_compact")
+
+
+def fk_stream_read(src, sink, stream=None) -> None:
+    """Measurement helper: stream-read the whole tensor `src` once (sink: >= 4 bytes of device memory)."""
+    _check(lib().fk_stream_read(_ptr(src), src.numel() * src.element_size(), _ptr(sink), _stream(stream)), "fk_stream_read")

@@ -18,7 +18,7 @@ namespace fk {
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
 typedef __attribute__((ext_vector_type(16))) float f32x16_t;
 
-static constexpr int kScoreThreads = 1024;  // four wavefronts per SIMD: MFMAs of one overlap the gelu of the others  // two wavefronts per SIMD: one's MFMAs overlap the other's gelu
+static constexpr int kScoreThreads = 1024;  // four wavefronts per SIMD: MFMAs of one overlap the gelu of the others
 static constexpr int kScoreWaves = kScoreThreads / kWave;
 static constexpr int kWPad = 8;  // bf16 elements of padding per transposed W1 row in LDS
 

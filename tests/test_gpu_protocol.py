@@ -154,3 +154,36 @@ def test_ragged_batch_shape_sampled_rows(gpu, ora):
     b_short = int(np.argmin(lens0))
     rows = [(b_long, 0), (b_short, 5)]
     assert lockstep(gpu, ora, w, 260, sample_rows=rows, scale=128.0 ** 0.5, check_every=32) >= 2
+
+
+def test_one_shot_prefill_compression(gpu, ora):
+    """Long-input use of the same calls (Section 4.3, long-context tasks: the cache is compressed once
+    after the prefill, no repeated eviction): a 65536-token prompt is scored, pruned to B = 2048
+    (128 newest protected) and compacted in one event, then decoding continues over the pruned cache."""
+    import paper_2602_03203_amd as fk
+    n, B, R = 65536, 2048, 128
+    w = si.config(1).scaled(batch=1, n_q_heads=8, n_kv_heads=2, prompt=n, budget=B, interval=R, ragged_max=n)
+    print(f"one-shot: building {n}-token prompt cache, capacity {w.capacity}", flush=True)
+    c = workload_cache(ora, w, lens=[n])
+    dev = gpu.DevCache(c, w.n_q_heads)
+    W1, b1, W2, b2 = scorer_storage(w)
+    fk.fk_score_kv(dev.desc, dev.K, dev.V, dev.len, n, *[gpu.to_dev(x) for x in (W1, b1, W2, b2)], dev.scores)
+    sc = ora.score_kv(c, W1, b1, W2, b2)
+    gpu.assert_scores_close(dev.scores.cpu().numpy(), sc, [n], "one-shot scores")
+    sc32 = sc.astype(np.float32)
+    keep_ref = ora.select_keep(sc32, c.pos, c.len, B, R, "sort")
+    dev.scores.copy_(torch.from_numpy(sc32).cuda())
+    keep = torch.full((1, 2, B), -1, dtype=torch.int32, device="cuda")
+    fk.fk_select_keep(dev.desc, dev.scores, dev.pos, dev.len, n, B, R, keep)
+    assert np.array_equal(keep.cpu().numpy(), keep_ref)
+    fk.fk_compact(dev.desc, dev.K, dev.V, dev.pos, dev.len, keep, B)
+    ora.compact(c, keep_ref, B)
+    h = dev.host(ora)
+    assert h.len[0] == B and np.array_equal(h.pos[:, :, :B], c.pos[:, :, :B])
+    assert np.array_equal(h.K[:, :, :B], c.K[:, :, :B]) and np.array_equal(h.V[:, :, :B], c.V[:, :, :B])
+    q, k_new, v_new, p_new = bulk_step_inputs(w, 0, 0, 3, [n])
+    for t in range(3):
+        fk.fk_decode_step(dev.desc, gpu.to_dev(q[t]), dev.K, dev.V, dev.pos, dev.len, gpu.to_dev(k_new[t]), gpu.to_dev(v_new[t]),
+                          gpu.to_dev(p_new[t]), B + 3, 128.0 ** 0.5, dev.out, dev.ws)
+        ora.append(c, k_new[t], v_new[t], p_new[t])
+        gpu.assert_attn_close(gpu.out_to_f64(dev.out), ora.decode_attn(c, q[t], 128.0 ** 0.5), "bf16", f"after one-shot, step {t}")
