@@ -39,6 +39,7 @@ def lib() -> ctypes.CDLL:
         build(force=False)
         _lib = ctypes.CDLL(_SO)
         _lib.ora_select_keep.restype = ctypes.c_int
+        _lib.ora_select_keep_sampled.restype = ctypes.c_int
         _lib.ora_append.restype = ctypes.c_int
         _lib.ora_max_threads.restype = ctypes.c_int
         _lib.ora_get_threads.restype = ctypes.c_int
@@ -139,6 +140,22 @@ def select_keep(scores: np.ndarray, pos: np.ndarray, length: np.ndarray, budget:
                                {"rank": 0, "sort": 1}[method], _p(keep))
     if rc != 0:
         raise RuntimeError(f"ora_select_keep failed ({rc})")
+    return keep
+
+
+def select_keep_sampled(scores: np.ndarray, noise: np.ndarray, pos: np.ndarray, length: np.ndarray, budget: int,
+                        recent: int, n_cand: int) -> np.ndarray:
+    """Top-K multinomial eviction (Section 3.1 Eq. 2, Appendix B.2) in Gumbel-top-k form: the ``n_cand``
+    lowest-scored non-recent pairs are candidates; of them the ``len - budget`` with the smallest fp32
+    ``score - noise`` are evicted.  scores, noise float32 [Bt,Hkv,cap].  Returns int32 [Bt,Hkv,budget]."""
+    Bt, Hkv, cap = scores.shape
+    assert scores.dtype == np.float32 and noise.dtype == np.float32 and noise.shape == scores.shape
+    keep = np.full((Bt, Hkv, budget), -1, np.int32)
+    rc = lib().ora_select_keep_sampled(Bt, Hkv, cap, _p(np.ascontiguousarray(scores)), _p(np.ascontiguousarray(noise)),
+                                       _p(np.ascontiguousarray(pos, np.int32)), _p(np.ascontiguousarray(length, np.int32)),
+                                       budget, recent, n_cand, _p(keep))
+    if rc != 0:
+        raise RuntimeError(f"ora_select_keep_sampled failed ({rc})")
     return keep
 
 

@@ -24,6 +24,11 @@
  *   ora_select_keep   keep the most recent R pairs and the top (B - R) of the others by
  *                     importance (Section 3.1, eviction protocol; Top_{B-L} of Eq. 5;
  *                     deterministic Top-K variant of the sampling ablation).
+ *   ora_select_keep_sampled
+ *                     Top-K multinomial eviction (Section 3.1 Eq. 2, Appendix B.2): the n_cand
+ *                     lowest-scored pairs are candidates, the evicted ones are drawn from them
+ *                     without replacement with probabilities softmax(-phi); the draw is taken in
+ *                     its Gumbel-top-k form on noise handed in by the caller.
  *   ora_compact       drop the evicted pairs, order preserved (Section 1: evicted pairs are
  *                     gone for good; the stable order is this build's definition).
  *   ora_append        one generated token joins every KV-head row (Section 3.1).
@@ -278,6 +283,71 @@ int ora_select_keep(int batch, int n_kv, int cap, const float *scores, const int
 #pragma omp atomic write
             rc = 2;
         }
+        free(kept);
+    }
+    return rc;
+}
+
+/* ------------------------------------------------------------------------- */
+/* sampled selection (Top-K multinomial eviction, Section 3.1 Eq. 2 / Appendix B.2)           */
+/* Row with n > budget entries, E = n - budget to evict, R newest protected:                  */
+/*   1. order the other n - R pairs by importance (score desc, position asc);                 */
+/*      the n_cand LAST of them (lowest scores) are the candidates (all, if fewer);            */
+/*      n_cand is raised to E when it is smaller.  The rest are safe.                          */
+/*   2. draw E of the candidates without replacement with probabilities softmax(-score).      */
+/*      Sequential draws with renormalisation have the same law as taking the E largest of     */
+/*      -score_i + g_i with g_i iid Gumbel(0,1) (Gumbel-top-k).  noise[] holds the g_i; the    */
+/*      perturbed key is formed in fp32, t_i = score_i - noise_i (= -(-score_i + noise_i)      */
+/*      exactly), so the E smallest t_i are evicted: the candidates are ordered by             */
+/*      (t desc, position asc) and the first n_cand - E stay.                                  */
+/* noise == 0 everywhere, or n_cand <= E, gives ora_select_keep's result.                      */
+/* ------------------------------------------------------------------------- */
+int ora_select_keep_sampled(int batch, int n_kv, int cap, const float *scores, const float *noise,
+                            const int32_t *pos, const int32_t *len, int budget, int R, int n_cand,
+                            int32_t *keep_idx) {
+    if (R > budget || budget > cap || R < 0 || n_cand < 0) return 1;
+    int rc = 0;
+#pragma omp parallel for num_threads(g_threads) schedule(dynamic, 1)
+    for (int row = 0; row < batch * n_kv; ++row) {
+        int b = row / n_kv;
+        int n = len[b];
+        int32_t *out = keep_idx + (int64_t)row * budget;
+        if (n <= budget) {
+            for (int j = 0; j < n; ++j) out[j] = j;
+            continue;
+        }
+        const float *sc = scores + (int64_t)row * cap;
+        const float *nz = noise + (int64_t)row * cap;
+        const int32_t *ps = pos + (int64_t)row * cap;
+        uint8_t *kept = (uint8_t *)calloc((size_t)n, 1);
+        cand_t *c = (cand_t *)malloc(sizeof(cand_t) * (size_t)n);
+        for (int i = 0; i < n; ++i) {
+            c[i].s = sc[i];
+            c[i].p = ps[i];
+            c[i].slot = i;
+        }
+        qsort(c, (size_t)n, sizeof(cand_t), cmp_pos_desc);
+        for (int i = 0; i < R; ++i) kept[c[i].slot] = 1;
+        int others = n - R, E = n - budget;
+        int K = n_cand < E ? E : n_cand;
+        if (K > others) K = others;
+        qsort(c + R, (size_t)others, sizeof(cand_t), cmp_importance);
+        for (int i = 0; i < others - K; ++i) kept[c[R + i].slot] = 1; /* safe */
+        cand_t *cd = c + R + (others - K);                              /* the K candidates */
+        for (int i = 0; i < K; ++i) cd[i].s = sc[cd[i].slot] - nz[cd[i].slot]; /* fp32 subtraction */
+        qsort(cd, (size_t)K, sizeof(cand_t), cmp_importance);
+        for (int i = 0; i < K - E; ++i) kept[cd[i].slot] = 1;
+        int cnt = 0;
+        for (int i = 0; i < n; ++i)
+            if (kept[i]) {
+                if (cnt < budget) out[cnt] = i;
+                ++cnt;
+            }
+        if (cnt != budget) {
+#pragma omp atomic write
+            rc = 2;
+        }
+        free(c);
         free(kept);
     }
     return rc;
