@@ -151,6 +151,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=256)
     ap.add_argument("--config", type=int, default=1)
     ap.add_argument("--prompt", type=int, default=None, help="override the prompt length (to start near the steady state)")
+    ap.add_argument("--policy", choices=["topk", "sampled"], default="topk",
+                    help="eviction action: deterministic top-k (default) or Top-K multinomial over 2L candidates")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--no-kernel-timing", action="store_true", help="skip the HIP-event pass over the attention launches")
     args = ap.parse_args()
@@ -197,6 +199,9 @@ def main():
     out = torch.empty((w.batch, w.n_q_heads, w.head_dim), dtype=desc.torch_dtype, device="cuda")
     scores = torch.zeros((w.batch, w.n_kv_heads, w.capacity), dtype=torch.float32, device="cuda")
     keep = torch.zeros((w.batch, w.n_kv_heads, B), dtype=torch.int32, device="cuda")
+    noise_pool = None
+    if args.policy == "sampled":   # Gumbel noise per slot, a pool of 8 independent draws cycled over the events
+        noise_pool = [dev(si.gen_gumbel(w.seed, (w.batch, w.n_kv_heads, w.capacity), event=e)) for e in range(8)]
     lens_at, _ = len_schedule(w, lens0, n_gen)
     max_at = lens_at.max(axis=1)
     scale = w.softmax_scale
@@ -215,7 +220,10 @@ def main():
                 ev_pairs[t // L][1].record(stream)
             if (t + 1) % L == 0:
                 fk.fk_score_kv(desc, Kc, Vc, lenc, ml, *dW, scores, stream)
-                fk.fk_select_keep(desc, scores, posc, lenc, ml, B, L, keep, stream)
+                if noise_pool is None:
+                    fk.fk_select_keep(desc, scores, posc, lenc, ml, B, L, keep, stream)
+                else:
+                    fk.fk_select_keep_sampled(desc, scores, noise_pool[(t // L) % 8], posc, lenc, ml, B, L, 2 * L, keep, stream)
                 fk.fk_compact(desc, Kc, Vc, posc, lenc, keep, B, stream)
 
     # warm-up (untimed), then restart from the prompt
@@ -244,7 +252,7 @@ def main():
         "dtype": w.dtype, "data": "synthetic",
         "config": {"workload": w.name, "batch": w.batch, "n_q_heads": w.n_q_heads, "n_kv_heads": w.n_kv_heads,
                    "head_dim": w.head_dim, "prompt": w.prompt, "budget": B, "eviction_interval": L,
-                   "capacity": w.capacity, "scorer_hidden": w.hidden},
+                   "capacity": w.capacity, "scorer_hidden": w.hidden, "eviction_policy": args.policy},
         "path_gbs_algorithmic": total_attn_bytes / wall / 1e9,
     }
 

@@ -140,6 +140,23 @@ fk_status fk_select_keep(const fk_cache_desc *desc, const float *scores, const i
                          int32_t protect_recent, int32_t *keep_idx, void *stream);
 
 /*
+ * Section 3.1 Eq. 2 and Appendix B.2 (Top-K multinomial eviction, the paper's inference policy).
+ * For every row with len[r] > budget, E = len[r] - budget pairs go: the last `protect_recent` live
+ * slots are kept; of the others, the max(n_candidates, E) lowest-ranked under (score descending,
+ * slot ascending) are candidates (the paper uses 2E), the rest are kept; E candidates are drawn
+ * without replacement with probabilities softmax(-score), in Gumbel-top-k form: the caller supplies
+ * noise[b][h][i] (iid Gumbel(0,1) for the paper's law; fp32, [batch][n_kv_heads][capacity]) and the
+ * E candidates with the smallest fp32 value of scores - noise are evicted, ties evicting the higher
+ * slot first.  noise == 0 or n_candidates <= E gives fk_select_keep's result.  Output, rows at or
+ * under budget, pos and the special values are as for fk_select_keep.  max_len <= 131072
+ * (FK_ERR_UNSUPPORTED above).
+ */
+fk_status fk_select_keep_sampled(const fk_cache_desc *desc, const float *scores, const float *noise,
+                                 const int32_t *pos, const int32_t *len, int32_t max_len,
+                                 int32_t budget, int32_t protect_recent, int32_t n_candidates,
+                                 int32_t *keep_idx, void *stream);
+
+/*
  * Section 1 / 3.1 (evicted pairs are discarded for good; stable in-place form): for every row
  * with len[r] > budget, slot j of K, V and pos receives the former contents of slot
  * keep_idx[b][h][j], j = 0 .. budget-1 (bit copies; keep_idx ascending with keep_idx[j] >= j,

@@ -20,7 +20,7 @@ FK_OK, FK_ERR_INVALID_ARG, FK_ERR_UNSUPPORTED, FK_ERR_WORKSPACE, FK_ERR_LAUNCH =
 FK_F32, FK_BF16 = 0, 1
 
 SYMBOLS = ["fk_status_string", "fk_version", "fk_append", "fk_decode_attn_workspace", "fk_decode_attn", "fk_decode_step",
-           "fk_score_kv", "fk_select_keep", "fk_compact", "fk_stream_read"]
+           "fk_score_kv", "fk_select_keep", "fk_select_keep_sampled", "fk_compact", "fk_stream_read"]
 
 
 class fk_cache_desc(ctypes.Structure):
@@ -59,6 +59,7 @@ def lib() -> ctypes.CDLL:
         L.fk_decode_step.restype, L.fk_decode_step.argtypes = ctypes.c_int, [dp, vp, vp, vp, vp, vp, vp, vp, vp, i32, f32, vp, vp, sz, vp]
         L.fk_score_kv.restype, L.fk_score_kv.argtypes = ctypes.c_int, [dp, vp, vp, vp, i32, sp, vp, vp]
         L.fk_select_keep.restype, L.fk_select_keep.argtypes = ctypes.c_int, [dp, vp, vp, vp, i32, i32, i32, vp, vp]
+        L.fk_select_keep_sampled.restype, L.fk_select_keep_sampled.argtypes = ctypes.c_int, [dp, vp, vp, vp, vp, i32, i32, i32, i32, vp, vp]
         L.fk_compact.restype, L.fk_compact.argtypes = ctypes.c_int, [dp, vp, vp, vp, vp, vp, i32, vp]
         L.fk_stream_read.restype, L.fk_stream_read.argtypes = ctypes.c_int, [vp, sz, vp, vp]
         _lib = L
@@ -151,6 +152,13 @@ def fk_select_keep(desc: CacheDesc, scores, pos, length, max_len: int, budget: i
                    stream=None) -> None:
     _check(lib().fk_select_keep(ctypes.byref(desc.c()), _ptr(scores), _ptr(pos), _ptr(length), int(max_len),
                                 int(budget), int(protect_recent), _ptr(keep_idx), _stream(stream)), "fk_select_keep")
+
+
+def fk_select_keep_sampled(desc: CacheDesc, scores, noise, pos, length, max_len: int, budget: int, protect_recent: int,
+                           n_candidates: int, keep_idx, stream=None) -> None:
+    _check(lib().fk_select_keep_sampled(ctypes.byref(desc.c()), _ptr(scores), _ptr(noise), _ptr(pos), _ptr(length),
+                                        int(max_len), int(budget), int(protect_recent), int(n_candidates),
+                                        _ptr(keep_idx), _stream(stream)), "fk_select_keep_sampled")
 
 
 def fk_compact(desc: CacheDesc, K, V, pos, length, keep_idx, budget: int, stream=None) -> None:

@@ -28,7 +28,7 @@ _C1 = np.uint64(0xBF58476D1CE4E5B9)
 _C2 = np.uint64(0x94D049BB133111EB)
 
 # tensor ids of the counter streams
-T_Q, T_K, T_V, T_W1, T_B1, T_W2, T_B2, T_FLAG, T_MIXMEAN, T_MIXSEL, T_LEN, T_SCORE = range(12)
+T_Q, T_K, T_V, T_W1, T_B1, T_W2, T_B2, T_FLAG, T_MIXMEAN, T_MIXSEL, T_LEN, T_SCORE, T_GUMBEL = range(13)
 
 BASE_SEED = 2602032030
 
@@ -295,3 +295,16 @@ def gen_scores(seed: int, shape, ties: int = 0) -> np.ndarray:
     if ties > 0:
         s = np.round(s * ties / 4.0) * (4.0 / ties)
     return s.astype(np.float32)
+
+
+def gen_gumbel(seed: int, shape, event: int = 0, levels: int = 0) -> np.ndarray:
+    """Standard Gumbel noise g = -log(-log u), float32, one value per cache slot, for the sampled
+    eviction policy; ``event`` selects an independent stream per eviction event.  ``levels`` > 0
+    quantises the noise so that exact ties with quantised scores occur."""
+    n = int(np.prod(shape))
+    u = uniform01(seed, T_GUMBEL, event, np.arange(n))
+    u = np.clip(u, 2.0 ** -53, 1.0 - 2.0 ** -53)
+    g = -np.log(-np.log(u)).reshape(shape)
+    if levels > 0:
+        g = np.round(g * levels / 4.0) * (4.0 / levels)
+    return g.astype(np.float32)

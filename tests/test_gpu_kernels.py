@@ -184,6 +184,43 @@ def test_select_keep_special_values(gpu, ora):
     assert keep[0, 3].cpu().tolist() == list(range(600)) + list(range(1100, 1200))
 
 
+SAMPLED_CASES = [
+    # Bt, Hkv, cap, lens, budget, recent, n_cand, ties (score levels), noise levels
+    (16, 8, 2176, [2176] * 16, 2048, 128, 256, 0, 0),        # the paper's policy at the benchmark shape: 2L candidates, L evicted
+    (2, 4, 2176, [2176, 2100], 2048, 128, 256, 6, 6),        # heavy ties in scores and in score - noise
+    (3, 2, 5000, [5000, 3001, 2999], 3000, 64, 3000, 3, 4),  # far over budget; one row just over; one under
+    (2, 2, 700, [700, 650], 500, 0, 100000, 0, 0),           # every non-recent pair is a candidate
+    (2, 2, 700, [700, 650], 500, 100, 0, 2, 2),              # n_cand below the number to evict: deterministic rule
+    (1, 3, 1500, [1500], 1, 0, 7, 2, 3),                     # budget 1
+    (2, 2, 40000, [40000, 33000], 8192, 128, 50000, 0, 0),   # long rows
+]
+
+
+@pytest.mark.parametrize("Bt,Hkv,cap,lens,budget,recent,n_cand,ties,nlev", SAMPLED_CASES)
+def test_select_keep_sampled_bit_exact(gpu, ora, Bt, Hkv, cap, lens, budget, recent, n_cand, ties, nlev):
+    import paper_2602_03203_amd as fk
+    print(f"sampled case Bt={Bt} Hkv={Hkv} cap={cap} lens={lens} B={budget} R={recent} K'={n_cand} ties={ties}/{nlev}", flush=True)
+    sc = si.gen_scores(4500 + cap + ties, (Bt, Hkv, cap), ties=ties)
+    noise = si.gen_gumbel(4600 + cap, (Bt, Hkv, cap), event=3, levels=nlev)
+    if ties:   # a few special values among the scores
+        flat = sc.reshape(-1)
+        idx = (si.hash_u64(2, si.T_FLAG, 0, np.arange(200)) % np.uint64(flat.size)).astype(np.int64)
+        flat[idx] = np.array([np.nan, np.inf, -np.inf, 0.0, -0.0], np.float32)[np.arange(200) % 5]
+    pos = np.tile(np.arange(cap, dtype=np.int32) * 2 + 3, (Bt, Hkv, 1))
+    ln = np.asarray(lens, np.int32)
+    ref = ora.select_keep_sampled(sc, noise, pos, ln, budget, recent, n_cand)
+    desc = fk.CacheDesc(Bt, Hkv, Hkv, 128, cap, "bf16")
+    keep = torch.full((Bt, Hkv, budget), -1, dtype=torch.int32, device="cuda")
+    dln = gpu.to_dev(np.repeat(ln[:, None], Hkv, 1))
+    fk.fk_select_keep_sampled(desc, gpu.to_dev(sc), gpu.to_dev(noise), gpu.to_dev(pos), dln, cap, budget, recent, n_cand, keep)
+    assert np.array_equal(keep.cpu().numpy(), ref)
+    # zero noise: the deterministic entry point's answer
+    det = torch.full_like(keep, -1)
+    fk.fk_select_keep(desc, gpu.to_dev(sc), None, dln, cap, budget, recent, det)
+    fk.fk_select_keep_sampled(desc, gpu.to_dev(sc), gpu.to_dev(np.zeros_like(noise)), None, dln, cap, budget, recent, n_cand, keep)
+    assert torch.equal(keep, det)
+
+
 COMPACT_CASES = [("f32", 64, 1, 2, 160, [160], 128), ("bf16", 128, 3, 2, 2176, [2176, 2050, 2048], 2048),
                  ("bf16", 64, 2, 3, 333, [333, 100], 150), ("f32", 128, 1, 1, 700, [700], 300)]
 

@@ -26,7 +26,7 @@ def gpu():
     return gpu_util
 
 
-def lockstep(gpu, ora, w, n_steps, sample_rows=None, scale=None, check_every=1, fused=True):
+def lockstep(gpu, ora, w, n_steps, sample_rows=None, scale=None, check_every=1, fused=True, sampled=False):
     """Run the device on the whole workload and the oracle on `sample_rows` [(b, h), ...]
     (None = every row).  Returns the number of events checked."""
     import paper_2602_03203_amd as fk
@@ -87,13 +87,21 @@ def lockstep(gpu, ora, w, n_steps, sample_rows=None, scale=None, check_every=1, 
                     assert np.array_equal(keep_own_h[b, h], k_own[0, 0]), f"own-score keep-set differs, row ({b},{h})"
             # both sides select on the oracle's scores
             dev.scores.copy_(torch.from_numpy(inject).cuda())
-            fk.fk_select_keep(dev.desc, dev.scores, dev.pos, dev.len, min(max_len, w.capacity), B, L, keep_dev)
+            if sampled:   # Top-K multinomial policy: 2L candidates, Gumbel noise per slot and event
+                noise = si.gen_gumbel(w.seed, (w.batch, w.n_kv_heads, w.capacity), event=events)
+                fk.fk_select_keep_sampled(dev.desc, dev.scores, gpu.to_dev(noise), dev.pos, dev.len, min(max_len, w.capacity),
+                                          B, L, 2 * L, keep_dev)
+            else:
+                fk.fk_select_keep(dev.desc, dev.scores, dev.pos, dev.len, min(max_len, w.capacity), B, L, keep_dev)
             keep_h = keep_dev.cpu().numpy()
             fk.fk_compact(dev.desc, dev.K, dev.V, dev.pos, dev.len, keep_dev, B)
             host = dev.host(ora)
             for (b, h), c in subs.items():
                 sc32, n = refs[(b, h)]
-                keep_ref = ora.select_keep(sc32, c.pos, c.len, B, L, "sort")
+                if sampled:
+                    keep_ref = ora.select_keep_sampled(sc32, np.ascontiguousarray(noise[b:b + 1, h:h + 1]), c.pos, c.len, B, L, 2 * L)
+                else:
+                    keep_ref = ora.select_keep(sc32, c.pos, c.len, B, L, "sort")
                 if n > B:
                     assert np.array_equal(keep_h[b, h], keep_ref[0, 0]), f"keep-set differs at step {t}, row ({b},{h})"
                 ora.compact(c, keep_ref, B)
@@ -187,3 +195,15 @@ def test_one_shot_prefill_compression(gpu, ora):
                           gpu.to_dev(p_new[t]), B + 3, 128.0 ** 0.5, dev.out, dev.ws)
         ora.append(c, k_new[t], v_new[t], p_new[t])
         gpu.assert_attn_close(gpu.out_to_f64(dev.out), ora.decode_attn(c, q[t], 128.0 ** 0.5), "bf16", f"after one-shot, step {t}")
+
+
+def test_sampled_policy_tiny_workload_full_run(gpu, ora):
+    """configs[0] end to end under the Top-K multinomial eviction policy (Section 3.1 Eq. 2): every event
+    draws the evicted pairs among the 2L lowest-scored ones; keep-sets and caches stay bit exact."""
+    w = si.config(0)
+    assert lockstep(gpu, ora, w, w.steps, sampled=True) == 16
+
+
+def test_sampled_policy_qwen3_shape_sampled_rows(gpu, ora):
+    w = si.config(1).scaled(prompt=1920)
+    assert lockstep(gpu, ora, w, 400, sample_rows=[(1, 2), (14, 5)], scale=128.0 ** 0.5, check_every=32, sampled=True) >= 2
