@@ -195,3 +195,90 @@ def run_protocol(c: Cache, step_inputs, n_steps: int, scorer, budget: int, inter
             sc, keep = evict(c, scorer, budget, interval, method)
             if on_event is not None:
                 on_event(t, sc, keep, before)
+
+
+# ---------------------------------------------------------------------------------------------
+# Attention features of the scoring model (Appendix B.1, "Attention Features")
+#
+# For every retained pair n and every query head h of its group, six numbers built from the
+# attention weights a_hat the pair has received:
+#   w8, w16, w32, wL : sums over the last 8 / 16 / 32 / L queries before the eviction event
+#                      (L = the update length; a window longer than the chunk is the whole chunk),
+#   cum              : sum over all chunks since the pair entered the cache (direct sum),
+#   dec              : the same with a decay of 0.9 per chunk, dec <- 0.9 dec + wL at every event.
+# a_n concatenates the six numbers of head 0, then head 1, ... (6 g values).
+# Readings (the paper gives one sentence): "attention scores" are the softmax weights; a chunk is
+# the L queries between two events; a pair appended mid-chunk starts from zero and counts the
+# weight of its own query.
+# ---------------------------------------------------------------------------------------------
+FEAT_WINDOWS = (8, 16, 32)
+FEAT_DECAY = 0.9
+W8, W16, W32, WL, CUM, DEC = range(6)
+
+
+def decode_attn_probs(c: Cache, q: np.ndarray, scale: float):
+    """decode_attn plus the attention weights: (out [Bt,Hq,D], probs [Bt,Hq,cap], 0 past len)."""
+    Bt, Hkv, cap, D = c.shape
+    _check_store(q, c.dtype)
+    Hq = q.shape[1]
+    out = np.empty((Bt, Hq, D), np.float64)
+    probs = np.zeros((Bt, Hq, cap), np.float64)
+    lib().ora_decode_attn_probs(_DT[c.dtype], Bt, Hq, Hkv, D, cap, _p(np.ascontiguousarray(q)), _p(c.K), _p(c.V),
+                                _p(c.len), ctypes.c_double(scale), _p(out), _p(probs))
+    return out, probs
+
+
+def new_feat(batch: int, n_kv: int, cap: int, g: int) -> np.ndarray:
+    """Feature state [Bt, Hkv, cap, g, 6] float64, all zero."""
+    return np.zeros((batch, n_kv, cap, g, 6), np.float64)
+
+
+def feat_step(feat: np.ndarray, probs: np.ndarray, lens_before: np.ndarray, chunk_pos: int, L: int) -> None:
+    """Account one query (chunk step ``chunk_pos`` in 0..L-1): every live slot gains its weight in wL
+    and in the windows that reach back to this step; the slot appended at this step starts from zero."""
+    Bt, Hkv, cap, g, _ = feat.shape
+    p = probs.reshape(Bt, Hkv, g, cap).transpose(0, 1, 3, 2)          # [Bt,Hkv,cap,g]
+    for b in range(Bt):
+        feat[b, :, int(lens_before[b])] = 0.0                        # the new pair's slot
+    feat[..., WL] += p
+    for plane, wnd in ((W8, 8), (W16, 16), (W32, 32)):
+        if chunk_pos >= L - wnd:
+            feat[..., plane] += p
+
+
+def feat_vectors(feat: np.ndarray) -> np.ndarray:
+    """The scorer's view at an event: [Bt,Hkv,cap,6g] with cum and dec already including this chunk."""
+    f = feat.copy()
+    f[..., CUM] = feat[..., CUM] + feat[..., WL]
+    f[..., DEC] = FEAT_DECAY * feat[..., DEC] + feat[..., WL]
+    Bt, Hkv, cap, g, _ = f.shape
+    return np.ascontiguousarray(f.reshape(Bt, Hkv, cap, 6 * g))
+
+
+def feat_roll_and_compact(feat: np.ndarray, keep_idx: np.ndarray, lens_before: np.ndarray, budget: int) -> None:
+    """Close the chunk: cum += wL, dec = 0.9 dec + wL, windows cleared; rows over budget are gathered
+    to the kept slots in order, like K and V."""
+    Bt, Hkv, cap, g, _ = feat.shape
+    feat[..., CUM] += feat[..., WL]
+    feat[..., DEC] = FEAT_DECAY * feat[..., DEC] + feat[..., WL]
+    feat[..., :4] = 0.0
+    for b in range(Bt):
+        if lens_before[b] > budget:
+            for h in range(Hkv):
+                feat[b, h, :budget] = feat[b, h, keep_idx[b, h]]
+                feat[b, h, budget:] = 0.0
+
+
+def score_kv_feat(c: Cache, fvec: np.ndarray, W1: np.ndarray, b1: np.ndarray, W2: np.ndarray, b2: np.ndarray) -> np.ndarray:
+    """Scorer on x = concat(k, v, a) (Section 3.1 Eq. 1).  fvec [Bt,Hkv,cap,A] float64; W1 [., 2D + A, H]."""
+    Bt, Hkv, cap, D = c.shape
+    _check_store(W1, c.dtype)
+    A = fvec.shape[-1]
+    nset, F, H = W1.shape
+    assert F == 2 * D + A and nset in (1, Hkv) and fvec.shape == (Bt, Hkv, cap, A) and fvec.dtype == np.float64
+    sc = np.full((Bt, Hkv, cap), np.nan, np.float64)
+    lib().ora_score_kv_feat(_DT[c.dtype], Bt, Hkv, D, cap, _p(c.K), _p(c.V), _p(np.ascontiguousarray(fvec)), A, _p(c.len),
+                            _p(np.ascontiguousarray(W1)), _p(np.ascontiguousarray(b1, np.float32)),
+                            _p(np.ascontiguousarray(W2, np.float32)), _p(np.ascontiguousarray(b2, np.float32)), H,
+                            int(nset == 1 and Hkv != 1), _p(sc))
+    return sc

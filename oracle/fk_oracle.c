@@ -21,6 +21,10 @@
  *   ora_score_kv      MLP scorer phi = sigma(x W1 + b1) W2 + b2 on x = concat(k, v)
  *                     (Appendix B.1, Model Design; Section 3.1 Eq. 1 without the
  *                     attention features), sigma = exact erf GELU.
+ *   ora_decode_attn_probs, ora_score_kv_feat
+ *                     the same two with the paper's attention features: the attention weights
+ *                     are returned per slot, and the scorer takes x = concat(k, v, a)
+ *                     (Appendix B.1); the feature bookkeeping itself is in __init__.py.
  *   ora_select_keep   keep the most recent R pairs and the top (B - R) of the others by
  *                     importance (Section 3.1, eviction protocol; Top_{B-L} of Eq. 5;
  *                     deterministic Top-K variant of the sampling ablation).
@@ -131,6 +135,42 @@ void ora_decode_attn(int dtype, int batch, int n_q, int n_kv, int D, int cap, co
     }
 }
 
+/* Same attention, also returning the weights a_hat (Appendix A) of every live slot:             */
+/* probs double [batch][n_q][cap], slots >= len untouched.  They feed the attention features    */
+/* of the scoring model (Appendix B.1, "Attention Features").                                   */
+void ora_decode_attn_probs(int dtype, int batch, int n_q, int n_kv, int D, int cap, const void *q,
+                           const void *K, const void *V, const int32_t *len, double scale,
+                           double *out, double *probs) {
+    int g = n_q / n_kv;
+#pragma omp parallel for num_threads(g_threads) schedule(dynamic, 1)
+    for (int bh = 0; bh < batch * n_q; ++bh) {
+        int b = bh / n_q, hq = bh % n_q, hk = hq / g;
+        int n = len[b];
+        int64_t row = (int64_t)b * n_kv + hk;
+        double *o = out + (int64_t)bh * D;
+        double *pr = probs + (int64_t)bh * cap;
+        for (int d = 0; d < D; ++d) o[d] = 0.0;
+        if (n <= 0) continue;
+        double m = -INFINITY;
+        for (int i = 0; i < n; ++i) {
+            double acc = 0.0;
+            for (int d = 0; d < D; ++d)
+                acc += ld(q, dtype, (int64_t)bh * D + d) * ld(K, dtype, (row * cap + i) * D + d);
+            pr[i] = scale * acc;
+            if (pr[i] > m) m = pr[i];
+        }
+        double z = 0.0;
+        for (int i = 0; i < n; ++i) {
+            pr[i] = exp(pr[i] - m);
+            z += pr[i];
+        }
+        for (int i = 0; i < n; ++i) {
+            pr[i] /= z;
+            for (int d = 0; d < D; ++d) o[d] += pr[i] * ld(V, dtype, (row * cap + i) * D + d);
+        }
+    }
+}
+
 /* ------------------------------------------------------------------------- */
 /* scorer: phi_n = sum_j gelu( sum_f x_{n,f} W1[f][j] + b1[j] ) W2[j] + b2,     */
 /*         x_n = [k_n, v_n]  (F = 2D)                                          */
@@ -161,6 +201,45 @@ void ora_score_kv(int dtype, int batch, int n_kv, int D, int cap, const void *K,
                 x[d] = ld(K, dtype, base + d);
                 x[D + d] = ld(V, dtype, base + d);
             }
+            double phi = 0.0;
+            for (int j = 0; j < H; ++j) {
+                double z = 0.0;
+                for (int f = 0; f < F; ++f) z += x[f] * w[(int64_t)j * F + f];
+                z += (double)b1[(int64_t)hw * H + j];
+                phi += gelu_erf(z) * (double)W2[(int64_t)hw * H + j];
+            }
+            scores[(int64_t)row * cap + i] = phi + (double)b2[hw];
+        }
+        free(x);
+        free(w);
+    }
+}
+
+/* Scorer on the paper's full input x_n = [k_n, v_n, a_n] (Section 3.1 Eq. 1, Appendix B.1):     */
+/* a_n = the A attention features of the pair (fp64 here), W1 [.][2D + A][H] storage type with   */
+/* the rows in the order k, v, a.                                                               */
+void ora_score_kv_feat(int dtype, int batch, int n_kv, int D, int cap, const void *K, const void *V,
+                       const double *feat /* [batch][n_kv][cap][A] */, int A, const int32_t *len,
+                       const void *W1, const float *b1, const float *W2, const float *b2, int H,
+                       int shared, double *scores) {
+    int F = 2 * D + A;
+#pragma omp parallel for num_threads(g_threads) schedule(dynamic, 1)
+    for (int row = 0; row < batch * n_kv; ++row) {
+        int b = row / n_kv, h = row % n_kv;
+        int hw = shared ? 0 : h;
+        int n = len[b];
+        double *x = (double *)malloc(sizeof(double) * (size_t)F);
+        double *w = (double *)malloc(sizeof(double) * (size_t)F * H);
+        for (int f = 0; f < F; ++f)
+            for (int j = 0; j < H; ++j)
+                w[(int64_t)j * F + f] = ld(W1, dtype, ((int64_t)hw * F + f) * H + j);
+        for (int i = 0; i < n; ++i) {
+            int64_t base = ((int64_t)row * cap + i) * D;
+            for (int d = 0; d < D; ++d) {
+                x[d] = ld(K, dtype, base + d);
+                x[D + d] = ld(V, dtype, base + d);
+            }
+            for (int a = 0; a < A; ++a) x[2 * D + a] = feat[((int64_t)row * cap + i) * A + a];
             double phi = 0.0;
             for (int j = 0; j < H; ++j) {
                 double z = 0.0;
