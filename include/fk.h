@@ -166,6 +166,55 @@ fk_status fk_compact(const fk_cache_desc *desc, void *K, void *V, int32_t *pos, 
                      const int32_t *keep_idx, int32_t budget, void *stream);
 
 /*
+ * ---- Attention features of the scoring model (Appendix B.1; bf16 with head_dim 128 only) ----
+ *
+ * Beside k and v the scorer sees, for every retained pair and every query head of its group, six sums of
+ * the attention weights the pair received: over the last 8, 16 and 32 queries of the current chunk of L
+ * steps, over the whole chunk so far (wL), and the sums carried over the earlier chunks, plain (cum)
+ * and decayed by 0.9 per chunk (dec).  Device state, owned by the caller, zero-filled at the start:
+ *   feat [batch][n_kv_heads][6][capacity][GP] fp32, GP = 4 if g <= 4 else 8 (heads >= g hold zeros),
+ *   planes in the order w8, w16, w32, wL, cum, dec; cum and dec hold the state BEFORE the current chunk.
+ * The scorer's feature vector of a pair is a[head * 6 + plane] with cum + wL and 0.9 dec + wL in the
+ * last two planes, so W1 has 2 * head_dim + 6 g rows: k, v, then a.
+ */
+
+/* Bytes of workspace fk_decode_step_feat needs (0 on bad args); no initialisation required. */
+size_t fk_decode_step_feat_workspace(const fk_cache_desc *desc);
+
+/*
+ * fk_decode_step that also accounts the step's attention weights (softmax over the retained set
+ * including the new pair, fp32 weights from the unrounded exponentials) in `feat`: the slot of the
+ * new pair restarts all six planes from zero, then every live slot i gains p[hq][i] in wL and in each
+ * window plane w with chunk_pos >= chunk_len - w.  chunk_pos = 0 .. chunk_len - 1 counts the steps since
+ * the last eviction event, chunk_len = L.  One launch, one workgroup per row.  The workspace holds the
+ * step's logits; calls sharing it must not overlap in time.
+ */
+fk_status fk_decode_step_feat(const fk_cache_desc *desc, const void *q, void *K, void *V, int32_t *pos,
+                              int32_t *len, const void *k_new, const void *v_new,
+                              const int32_t *pos_new, int32_t max_len, float softmax_scale, float *feat,
+                              int32_t chunk_pos, int32_t chunk_len, void *out, void *workspace,
+                              size_t workspace_bytes, void *stream);
+
+/*
+ * fk_score_kv on x = concat(k, v, a) (Section 3.1 Eq. 1 with the attention features of Appendix
+ * B.1).  scorer->w1 is [n_sets][2*head_dim + 6 g][hidden]; the fp32 features enter the contraction as
+ * a bf16 head plus a bf16 remainder (16 significant bits).  FK_ERR_UNSUPPORTED unless hidden is a
+ * multiple of 32 and hidden * (2*head_dim + roundup(6 g, 16) + 8) * 2 + 8 * hidden <= 160 KiB.
+ */
+fk_status fk_score_kv_feat(const fk_cache_desc *desc, const void *K, const void *V, const float *feat,
+                           const int32_t *len, int32_t max_len, const fk_scorer *scorer, float *scores,
+                           void *stream);
+
+/*
+ * fk_compact that also closes the chunk of the features: for every row and live slot cum += wL,
+ * dec = 0.9 dec + wL, the planes w8, w16, w32, wL restart from zero, and rows over budget move the
+ * features of slot keep_idx[j] to slot j together with K, V and pos.  Other arguments and results as
+ * fk_compact.
+ */
+fk_status fk_compact_feat(const fk_cache_desc *desc, void *K, void *V, int32_t *pos, float *feat,
+                          int32_t *len, const int32_t *keep_idx, int32_t budget, void *stream);
+
+/*
  * Measurement helper, not part of the method: reads `bytes` (>= 16) of device memory at `src` with
  * 16-byte loads and discards them; `sink` is 4 bytes of device memory.  bench.py times it to report
  * the achievable streaming bandwidth of the box beside the nominal HBM peak.

@@ -20,7 +20,8 @@ FK_OK, FK_ERR_INVALID_ARG, FK_ERR_UNSUPPORTED, FK_ERR_WORKSPACE, FK_ERR_LAUNCH =
 FK_F32, FK_BF16 = 0, 1
 
 SYMBOLS = ["fk_status_string", "fk_version", "fk_append", "fk_decode_attn_workspace", "fk_decode_attn", "fk_decode_step",
-           "fk_score_kv", "fk_select_keep", "fk_select_keep_sampled", "fk_compact", "fk_stream_read"]
+           "fk_score_kv", "fk_select_keep", "fk_select_keep_sampled", "fk_compact", "fk_decode_step_feat_workspace",
+           "fk_decode_step_feat", "fk_score_kv_feat", "fk_compact_feat", "fk_stream_read"]
 
 
 class fk_cache_desc(ctypes.Structure):
@@ -61,6 +62,10 @@ def lib() -> ctypes.CDLL:
         L.fk_select_keep.restype, L.fk_select_keep.argtypes = ctypes.c_int, [dp, vp, vp, vp, i32, i32, i32, vp, vp]
         L.fk_select_keep_sampled.restype, L.fk_select_keep_sampled.argtypes = ctypes.c_int, [dp, vp, vp, vp, vp, i32, i32, i32, i32, vp, vp]
         L.fk_compact.restype, L.fk_compact.argtypes = ctypes.c_int, [dp, vp, vp, vp, vp, vp, i32, vp]
+        L.fk_decode_step_feat_workspace.restype, L.fk_decode_step_feat_workspace.argtypes = sz, [dp]
+        L.fk_decode_step_feat.restype, L.fk_decode_step_feat.argtypes = ctypes.c_int, [dp, vp, vp, vp, vp, vp, vp, vp, vp, i32, f32, vp, i32, i32, vp, vp, sz, vp]
+        L.fk_score_kv_feat.restype, L.fk_score_kv_feat.argtypes = ctypes.c_int, [dp, vp, vp, vp, vp, i32, sp, vp, vp]
+        L.fk_compact_feat.restype, L.fk_compact_feat.argtypes = ctypes.c_int, [dp, vp, vp, vp, vp, vp, vp, i32, vp]
         L.fk_stream_read.restype, L.fk_stream_read.argtypes = ctypes.c_int, [vp, sz, vp, vp]
         _lib = L
     return _lib
@@ -164,6 +169,43 @@ def fk_select_keep_sampled(desc: CacheDesc, scores, noise, pos, length, max_len:
 def fk_compact(desc: CacheDesc, K, V, pos, length, keep_idx, budget: int, stream=None) -> None:
     _check(lib().fk_compact(ctypes.byref(desc.c()), _ptr(K), _ptr(V), _ptr(pos), _ptr(length), _ptr(keep_idx),
                             int(budget), _stream(stream)), "fk_compact")
+
+
+def feat_heads(desc: CacheDesc) -> int:
+    """Heads per slot in the attention-feature state (the group size padded to 4 or 8)."""
+    return 4 if desc.n_q_heads // desc.n_kv_heads <= 4 else 8
+
+
+def new_feat(desc: CacheDesc) -> "torch.Tensor":
+    """Zero attention-feature state [batch, n_kv_heads, 6, capacity, GP] fp32."""
+    return torch.zeros((desc.batch, desc.n_kv_heads, 6, desc.capacity, feat_heads(desc)), dtype=torch.float32, device="cuda")
+
+
+def new_feat_workspace(desc: CacheDesc) -> "torch.Tensor":
+    return torch.zeros(max(int(lib().fk_decode_step_feat_workspace(ctypes.byref(desc.c()))), 16), dtype=torch.uint8, device="cuda")
+
+
+def fk_decode_step_feat(desc: CacheDesc, q, K, V, pos, length, k_new, v_new, pos_new, max_len: int, softmax_scale: float,
+                        feat, chunk_pos: int, chunk_len: int, out, workspace, stream=None) -> None:
+    """fk_decode_step that also accounts the step's attention weights in the feature state."""
+    nbytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(lib().fk_decode_step_feat(ctypes.byref(desc.c()), _ptr(q), _ptr(K), _ptr(V), _ptr(pos), _ptr(length),
+                                     _ptr(k_new), _ptr(v_new), _ptr(pos_new), int(max_len), float(softmax_scale),
+                                     _ptr(feat), int(chunk_pos), int(chunk_len), _ptr(out), _ptr(workspace), nbytes,
+                                     _stream(stream)), "fk_decode_step_feat")
+
+
+def fk_score_kv_feat(desc: CacheDesc, K, V, feat, length, max_len: int, W1, b1, W2, b2, scores, stream=None) -> None:
+    """fk_score_kv on concat(k, v, a); W1 [n_sets, 2D + 6g, H]."""
+    n_sets, _, hidden = W1.shape
+    sc = fk_scorer(_ptr(W1), _ptr(b1), _ptr(W2), _ptr(b2), int(hidden), 1 if n_sets == desc.n_kv_heads and n_sets > 1 else 0)
+    _check(lib().fk_score_kv_feat(ctypes.byref(desc.c()), _ptr(K), _ptr(V), _ptr(feat), _ptr(length), int(max_len),
+                                  ctypes.byref(sc), _ptr(scores), _stream(stream)), "fk_score_kv_feat")
+
+
+def fk_compact_feat(desc: CacheDesc, K, V, pos, feat, length, keep_idx, budget: int, stream=None) -> None:
+    _check(lib().fk_compact_feat(ctypes.byref(desc.c()), _ptr(K), _ptr(V), _ptr(pos), _ptr(feat), _ptr(length),
+                                 _ptr(keep_idx), int(budget), _stream(stream)), "fk_compact_feat")
 
 
 def fk_stream_read(src, sink, stream=None) -> None:

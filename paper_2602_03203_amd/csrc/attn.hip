@@ -83,6 +83,8 @@ template <typename T, int D, int G> struct AttnCfg {
     static constexpr size_t LDS_BYTES =
         sizeof(float) * ((size_t)NG * G * D + 3 * (size_t)NG * G + 8 + (size_t)WAVES * KT * GP + (size_t)WAVES * GP + 4) +
         (PVM ? (size_t)WAVES * KT * KRS : 0);
+    // attention-feature variant (PVM only): lx [NG][G] exact normaliser partials | invL [8], behind the K tiles
+    static constexpr size_t LDS_BYTES_FEAT = LDS_BYTES + sizeof(float) * ((size_t)NG * G + 8);
 };
 
 struct AttnPlan {
@@ -135,11 +137,29 @@ struct AttnParams {
     float* rec;          // [rows][nsplit][G][D + 2]
     uint32_t* row_cnt;   // [rows], zero between launches
     void* out;
+    // attention features (Appendix B.1), only read by the feature variant of the kernel
+    float* feat;      // [rows][6][cap][GP]
+    float* logit;     // [rows][cap][GP] scratch: base-2 logits of this step
+    int chunk_pos, chunk_len;
 };
 
-template <typename T, int D, int G>
+// planes of the feature state: sums of this chunk's attention weights over the last 8 / 16 / 32
+// queries and over the whole chunk, then the sums carried over the earlier chunks (plain, 0.9-decayed)
+enum { FEAT_W8 = 0, FEAT_W16, FEAT_W32, FEAT_WL, FEAT_CUM, FEAT_DEC, FEAT_PLANES };
+
+__device__ __forceinline__ void feat_add(float4* dst, const float4 p) {
+    const float4 v = *dst;
+    *dst = make_float4(v.x + p.x, v.y + p.y, v.z + p.z, v.w + p.w);
+}
+
+__device__ __forceinline__ float4 keep_if(bool c, const float4 p) {
+    return make_float4(c ? p.x : 0.f, c ? p.y : 0.f, c ? p.z : 0.f, c ? p.w : 0.f);
+}
+
+template <typename T, int D, int G, bool FEAT>
 __global__ __launch_bounds__((AttnCfg<T, D, G>::THREADS)) void attn_kernel(const AttnParams P) {
     using C = AttnCfg<T, D, G>;
+    static_assert(!FEAT || C::PVM, "the feature variant exists for bf16, D = 128 only");
     constexpr int CH = C::CH, KG = C::KG, WAVES = C::WAVES, KT = C::KT, VU = C::VU, EPL = C::EPL, GP = C::GP, NG = C::NG;
     const int row = blockIdx.y, split = blockIdx.x;
     const int b = row / P.n_kv, hkv = row % P.n_kv;
@@ -256,12 +276,14 @@ __global__ __launch_bounds__((AttnCfg<T, D, G>::THREADS)) void attn_kernel(const
             if (n16 < G) qa[ks].u = *reinterpret_cast<const uint4*>(qrow + (size_t)n16 * D + ks * 32 + quad * 8);
             else qa[ks].u = make_uint4(0, 0, 0, 0);
         }
-        float m_run[4], l_run[4];
+        float m_run[4], l_run[4], lx_run[4];  // lx: sum of the unrounded weights (feature variant)
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             m_run[i] = kNegBig;
             l_run[i] = 0.f;
+            lx_run[i] = 0.f;
         }
+        float* lg_row = FEAT ? P.logit + (size_t)row * P.cap * GP : nullptr;
         f32x4_t o[8];  // o[e][i] = out[head quad*4 + i][channel n16*8 + e], un-normalised
 #pragma unroll
         for (int e = 0; e < 8; ++e) o[e] = (f32x4_t){0.f, 0.f, 0.f, 0.f};
@@ -299,6 +321,16 @@ __global__ __launch_bounds__((AttnCfg<T, D, G>::THREADS)) void attn_kernel(const
             bool changed = false;
             float corr[4];
             uint32_t pb[2][4];
+            if constexpr (FEAT) {  // keep the step's logits: the second pass turns them into attention weights
+                if (quad * 4 < GP) {
+                    if (base + n16 < end)
+                        *reinterpret_cast<float4*>(lg_row + (size_t)(base + n16) * GP + quad * 4) =
+                            make_float4(c[0][0] * P.scale_log2e, c[0][1] * P.scale_log2e, c[0][2] * P.scale_log2e, c[0][3] * P.scale_log2e);
+                    if (base + 16 + n16 < end)
+                        *reinterpret_cast<float4*>(lg_row + (size_t)(base + 16 + n16) * GP + quad * 4) =
+                            make_float4(c[1][0] * P.scale_log2e, c[1][1] * P.scale_log2e, c[1][2] * P.scale_log2e, c[1][3] * P.scale_log2e);
+                }
+            }
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
                 const float s0 = (base + n16 < end) ? c[0][i] * P.scale_log2e : kNegBig;
@@ -307,10 +339,12 @@ __global__ __launch_bounds__((AttnCfg<T, D, G>::THREADS)) void attn_kernel(const
                 changed |= mn > m_run[i];
                 corr[i] = exp2f(m_run[i] - mn);
                 // probabilities rounded to bf16; the SAME rounded values go into l, so the weights stay normalised
-                const uint32_t u0 = __float_as_uint(exp2f(s0 - mn)) + 0x8000u, u1 = __float_as_uint(exp2f(s1 - mn)) + 0x8000u;
+                const float e0 = exp2f(s0 - mn), e1 = exp2f(s1 - mn);
+                const uint32_t u0 = __float_as_uint(e0) + 0x8000u, u1 = __float_as_uint(e1) + 0x8000u;
                 pb[0][i] = u0 >> 16;
                 pb[1][i] = u1 >> 16;
                 l_run[i] = l_run[i] * corr[i] + __uint_as_float(u0 & 0xffff0000u) + __uint_as_float(u1 & 0xffff0000u);
+                if constexpr (FEAT) lx_run[i] = lx_run[i] * corr[i] + e0 + e1;
                 m_run[i] = mn;
             }
             if (quad * 4 < GP) {
@@ -357,6 +391,11 @@ __global__ __launch_bounds__((AttnCfg<T, D, G>::THREADS)) void attn_kernel(const
                     s_m[wave * G + h] = m_run[i];
                     s_l[wave * G + h] = ls;
                 }
+            }
+            if constexpr (FEAT) {
+                const float lxs = group_sum<16>(lx_run[i]);
+                float* s_lx = reinterpret_cast<float*>(reinterpret_cast<unsigned char*>(s_corr + WAVES * GP + 4) + (size_t)WAVES * KT * KRS);
+                if (h < G && n16 == 0) s_lx[wave * G + h] = lxs;
             }
         }
     } else if constexpr (C::MFMA) {
@@ -581,12 +620,77 @@ __global__ __launch_bounds__((AttnCfg<T, D, G>::THREADS)) void attn_kernel(const
             }
         }
     }
+    if constexpr (FEAT) {
+        // Second pass (one workgroup per row): weight of key i for head h = 2^(s_i - M_h) / L_h with the
+        // merged maximum M_h and the exact (unrounded) normaliser L_h.  Every live slot gains its weight
+        // in the chunk plane and in the windows that reach back to this step; the slot appended at this
+        // step starts all six planes afresh.
+        float* s_lx = reinterpret_cast<float*>(reinterpret_cast<unsigned char*>(s_corr + WAVES * GP + 4) + (size_t)WAVES * C::KT * C::KRS);
+        float* s_invL = s_lx + NG * G;
+        if (tid < G) {
+            float ls = 0.f;
+#pragma unroll 8
+            for (int g2 = 0; g2 < NG; ++g2) ls = fmaf(s_lx[g2 * G + tid], s_w[g2 * G + tid], ls);
+            s_invL[tid] = 1.0f / ls;
+        }
+        __syncthreads();  // also: the logits stored above by other waves of this workgroup are visible
+        const float* lg_row = P.logit + (size_t)row * P.cap * GP;
+        float* frow = P.feat + (size_t)row * FEAT_PLANES * P.cap * GP;
+        constexpr int Q4 = GP / 4;
+        const size_t pl4 = (size_t)P.cap * Q4;  // float4 units per plane
+        const bool on8 = P.chunk_pos >= P.chunk_len - 8, on16 = P.chunk_pos >= P.chunk_len - 16,
+                   on32 = P.chunk_pos >= P.chunk_len - 32;
+        const float4 zero = make_float4(0.f, 0.f, 0.f, 0.f);
+        for (int t = tid; t < n * Q4; t += C::THREADS) {
+            const int i = t / Q4, h0 = (t % Q4) * 4;
+            const float4 s = *reinterpret_cast<const float4*>(lg_row + (size_t)i * GP + h0);
+            float4 p;
+            p.x = h0 + 0 < G ? exp2f(s.x - s_M[h0 + 0]) * s_invL[h0 + 0] : 0.f;
+            p.y = h0 + 1 < G ? exp2f(s.y - s_M[h0 + 1]) * s_invL[h0 + 1] : 0.f;
+            p.z = h0 + 2 < G ? exp2f(s.z - s_M[h0 + 2]) * s_invL[h0 + 2] : 0.f;
+            p.w = h0 + 3 < G ? exp2f(s.w - s_M[h0 + 3]) * s_invL[h0 + 3] : 0.f;
+            float4* f = reinterpret_cast<float4*>(frow + (size_t)i * GP + h0);
+            if (i == new_slot) {
+                f[FEAT_W8 * pl4] = keep_if(on8, p);
+                f[FEAT_W16 * pl4] = keep_if(on16, p);
+                f[FEAT_W32 * pl4] = keep_if(on32, p);
+                f[FEAT_WL * pl4] = p;
+                f[FEAT_CUM * pl4] = zero;
+                f[FEAT_DEC * pl4] = zero;
+            } else {
+                feat_add(f + FEAT_WL * pl4, p);
+                if (on32) feat_add(f + FEAT_W32 * pl4, p);
+                if (on16) feat_add(f + FEAT_W16 * pl4, p);
+                if (on8) feat_add(f + FEAT_W8 * pl4, p);
+            }
+        }
+    }
     finish(used > 1);
 }
 
 template <typename T, int D, int G>
 static fk_status attn_launch(const fk_cache_desc* d, const AttnParams& base, int max_len, void* ws, hipStream_t st) {
     using C = AttnCfg<T, D, G>;
+    if constexpr (C::PVM) {
+        if (base.feat) {  // feature variant: one workgroup per row, the logit scratch sits behind the counters
+            AttnParams P = base;
+            P.split_len = (d->capacity + 31) / 32 * 32;  // the whole row, whatever max_len says
+            P.nsplit = 1;
+            P.row_cnt = reinterpret_cast<uint32_t*>(ws);
+            P.rec = nullptr;
+            P.logit = reinterpret_cast<float*>(reinterpret_cast<char*>(ws) + attn_counter_bytes(d));
+            auto kern = attn_kernel<T, D, G, true>;
+            static bool attr_set = false;
+            if (!attr_set) {
+                if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)C::LDS_BYTES_FEAT) != hipSuccess)
+                    return FK_ERR_LAUNCH;
+                attr_set = true;
+            }
+            hipLaunchKernelGGL(kern, dim3(1, d->batch * d->n_kv_heads), dim3(C::THREADS), C::LDS_BYTES_FEAT, st, P);
+            return launch_status();
+        }
+    }
+    if (base.feat) return FK_ERR_UNSUPPORTED;
     const AttnPlan p = attn_plan(d, max_len);
     const int rows = d->batch * d->n_kv_heads;
     AttnParams P = base;
@@ -594,7 +698,7 @@ static fk_status attn_launch(const fk_cache_desc* d, const AttnParams& base, int
     P.nsplit = p.nsplit;
     P.row_cnt = reinterpret_cast<uint32_t*>(ws);
     P.rec = reinterpret_cast<float*>(reinterpret_cast<char*>(ws) + attn_counter_bytes(d));
-    auto kern = attn_kernel<T, D, G>;
+    auto kern = attn_kernel<T, D, G, false>;
     static bool attr_set = false;  // per template instantiation
     if (!attr_set) {
         if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)C::LDS_BYTES) != hipSuccess)
@@ -620,10 +724,15 @@ static fk_status attn_dispatch_g(int g, const fk_cache_desc* d, const AttnParams
     return FK_ERR_UNSUPPORTED;
 }
 
+static size_t feat_workspace_bytes(const fk_cache_desc* d) {
+    const size_t g = d->n_q_heads / d->n_kv_heads;
+    return attn_counter_bytes(d) + (size_t)d->batch * d->n_kv_heads * d->capacity * (g <= 4 ? 4 : 8) * sizeof(float);
+}
+
 static fk_status attn_entry(const fk_cache_desc* desc, AttnParams P, int max_len, float softmax_scale, void* workspace,
                             size_t workspace_bytes, void* stream) {
     if (max_len <= 0 || max_len > desc->capacity) return FK_ERR_INVALID_ARG;
-    const size_t need = fk_decode_attn_workspace(desc, max_len);
+    const size_t need = P.feat ? feat_workspace_bytes(desc) : fk_decode_attn_workspace(desc, max_len);
     if (!workspace || workspace_bytes < need || !aligned16(workspace)) return FK_ERR_WORKSPACE;
     const int g = desc->n_q_heads / desc->n_kv_heads;
     P.scale_log2e = softmax_scale * 1.4426950408889634f;
@@ -685,5 +794,39 @@ extern "C" fk_status fk_decode_step(const fk_cache_desc* desc, const void* q, vo
     P.v_new = v_new;
     P.pos_new = pos_new;
     P.out = out;
+    return attn_entry(desc, P, max_len, softmax_scale, workspace, workspace_bytes, stream);
+}
+
+extern "C" size_t fk_decode_step_feat_workspace(const fk_cache_desc* desc) {
+    if (check_desc(desc) != FK_OK) return 0;
+    return feat_workspace_bytes(desc);
+}
+
+extern "C" fk_status fk_decode_step_feat(const fk_cache_desc* desc, const void* q, void* K, void* V, int32_t* pos,
+                                         int32_t* len, const void* k_new, const void* v_new, const int32_t* pos_new,
+                                         int32_t max_len, float softmax_scale, float* feat, int32_t chunk_pos,
+                                         int32_t chunk_len, void* out, void* workspace, size_t workspace_bytes,
+                                         void* stream) {
+    fk_status s = check_desc(desc);
+    if (s != FK_OK) return s;
+    if (!q || !K || !V || !pos || !len || !k_new || !v_new || !pos_new || !out || !feat) return FK_ERR_INVALID_ARG;
+    if (!aligned16(q) || !aligned16(K) || !aligned16(V) || !aligned16(out) || !aligned16(k_new) || !aligned16(v_new) ||
+        !aligned16(feat))
+        return FK_ERR_INVALID_ARG;
+    if (chunk_len <= 0 || chunk_pos < 0 || chunk_pos >= chunk_len) return FK_ERR_INVALID_ARG;
+    if (desc->dtype != FK_BF16 || desc->head_dim != 128) return FK_ERR_UNSUPPORTED;
+    AttnParams P = {};
+    P.q = q;
+    P.K = K;
+    P.V = V;
+    P.pos = pos;
+    P.len = len;
+    P.k_new = k_new;
+    P.v_new = v_new;
+    P.pos_new = pos_new;
+    P.out = out;
+    P.feat = feat;
+    P.chunk_pos = chunk_pos;
+    P.chunk_len = chunk_len;
     return attn_entry(desc, P, max_len, softmax_scale, workspace, workspace_bytes, stream);
 }

@@ -97,6 +97,62 @@ __global__ __launch_bounds__(kCompactThreads) void compact_kernel(uint4* __restr
     }
 }
 
+// ---------------------------------------------------------------------------------------
+// close a chunk of the attention features (Appendix B.1) and compact them with the cache
+//
+// feat [rows][6][cap][GP]: planes w8, w16, w32, wL (sums of this chunk's attention weights over
+// the last 8 / 16 / 32 queries and over the whole chunk), cum, dec (sums carried over earlier
+// chunks, plain and decayed by 0.9 per chunk).  At the end of a chunk cum += wL, dec = 0.9 dec
+// + wL and the four chunk planes restart from zero; rows over budget move slot keep[j] to slot
+// j in the same pass (ascending tiles, all sources of a tile read before it is written: the
+// argument of compact_kernel).  One workgroup per row; a thread owns 4 heads of a slot.
+// ---------------------------------------------------------------------------------------
+static constexpr float kFeatDecay = 0.9f;
+
+template <int Q4 /* float4 units per slot */>
+__global__ __launch_bounds__(kCompactThreads) void feat_roll_kernel(float4* __restrict__ feat,
+                                                                    const int32_t* __restrict__ len,
+                                                                    const int32_t* __restrict__ keep, int cap,
+                                                                    int budget) {
+    const int row = blockIdx.x;
+    const int n = min(len[row], cap);
+    if (n <= 0) return;
+    const size_t pl4 = (size_t)cap * Q4;
+    float4* f = feat + (size_t)row * 6 * pl4;
+    float4 *wl = f + 3 * pl4, *cum = f + 4 * pl4, *dec = f + 5 * pl4;
+    const bool gather = n > budget;
+    const int32_t* kp = keep + (size_t)row * budget;
+    const int n_out = gather ? budget : n;
+    constexpr int tile = kCompactThreads / Q4;  // slots per pass
+    const int sl = threadIdx.x / Q4, q = threadIdx.x % Q4;
+    for (int base = 0; base < n_out; base += tile) {
+        const int j = base + sl;
+        int src = -1;
+        if (j < n_out) src = gather ? kp[j] : j;
+        const bool ok = src >= 0 && src < n;
+        float4 c = make_float4(0.f, 0.f, 0.f, 0.f), d = c, w = c;
+        if (ok) {
+            c = cum[(size_t)src * Q4 + q];
+            d = dec[(size_t)src * Q4 + q];
+            w = wl[(size_t)src * Q4 + q];
+        }
+        __syncthreads();
+        if (ok) {
+            cum[(size_t)j * Q4 + q] = make_float4(c.x + w.x, c.y + w.y, c.z + w.z, c.w + w.w);
+            dec[(size_t)j * Q4 + q] = make_float4(fmaf(kFeatDecay, d.x, w.x), fmaf(kFeatDecay, d.y, w.y),
+                                                  fmaf(kFeatDecay, d.z, w.z), fmaf(kFeatDecay, d.w, w.w));
+        }
+    }
+    __syncthreads();  // every wL source has been read
+    const float4 zero = make_float4(0.f, 0.f, 0.f, 0.f);
+    for (int t = threadIdx.x; t < n * Q4; t += kCompactThreads) {
+        f[t] = zero;
+        f[pl4 + t] = zero;
+        f[2 * pl4 + t] = zero;
+        f[3 * pl4 + t] = zero;
+    }
+}
+
 // after every row has been compacted: len[row] = min(len[row], budget)
 __global__ void clamp_len_kernel(int32_t* __restrict__ len, int rows, int budget) {
     const int r = blockIdx.x * blockDim.x + threadIdx.x;
@@ -132,6 +188,29 @@ extern "C" fk_status fk_compact(const fk_cache_desc* desc, void* K, void* V, int
     hipStream_t st = (hipStream_t)stream;
     hipLaunchKernelGGL(compact_kernel, dim3(rows, 2 * (chunks / kSliceChunks) + 1), dim3(kCompactThreads), 0, st, (uint4*)K, (uint4*)V,
                        pos, len, keep_idx, desc->capacity, budget, chunks);
+    hipLaunchKernelGGL(clamp_len_kernel, dim3((rows + 255) / 256), dim3(256), 0, st, len, rows, budget);
+    return launch_status();
+}
+
+extern "C" fk_status fk_compact_feat(const fk_cache_desc* desc, void* K, void* V, int32_t* pos, float* feat,
+                                     int32_t* len, const int32_t* keep_idx, int32_t budget, void* stream) {
+    fk_status s = check_desc(desc);
+    if (s != FK_OK) return s;
+    if (!K || !V || !pos || !feat || !len || !keep_idx) return FK_ERR_INVALID_ARG;
+    if (budget <= 0 || budget > desc->capacity) return FK_ERR_INVALID_ARG;
+    if (!aligned16(K) || !aligned16(V) || !aligned16(feat)) return FK_ERR_INVALID_ARG;
+    const int chunks = desc->head_dim * (desc->dtype == FK_F32 ? 4 : 2) / 16;
+    const int rows = desc->batch * desc->n_kv_heads;
+    const int g = desc->n_q_heads / desc->n_kv_heads;
+    hipStream_t st = (hipStream_t)stream;
+    hipLaunchKernelGGL(compact_kernel, dim3(rows, 2 * (chunks / kSliceChunks) + 1), dim3(kCompactThreads), 0, st, (uint4*)K, (uint4*)V,
+                       pos, len, keep_idx, desc->capacity, budget, chunks);
+    if (g <= 4)
+        hipLaunchKernelGGL(feat_roll_kernel<1>, dim3(rows), dim3(kCompactThreads), 0, st, (float4*)feat, len, keep_idx,
+                           desc->capacity, budget);
+    else
+        hipLaunchKernelGGL(feat_roll_kernel<2>, dim3(rows), dim3(kCompactThreads), 0, st, (float4*)feat, len, keep_idx,
+                           desc->capacity, budget);
     hipLaunchKernelGGL(clamp_len_kernel, dim3((rows + 255) / 256), dim3(256), 0, st, len, rows, budget);
     return launch_status();
 }

@@ -11,6 +11,11 @@
 //   C tile    = lane holds 16 hidden units of ONE pair, so bias, gelu, the W2 dot and the
 //               reduction over the hidden dimension stay in registers (one cross-half add).
 // fp32 path: plain fp32 FMA (the fp32 matrix rate equals the vector rate on this chip).
+//
+// fk_score_kv_feat: x = concat(k, v, a) with the 6 g attention features of the pair (Appendix B.1).
+// The features are fp32 state; each is split into a bf16 head and a bf16 remainder (x = hi + lo, 16
+// significant bits) and both parts are multiplied with the same W1^T tile, so the contraction stays
+// on the matrix cores without rounding the features to 8 bits.
 #include "fk_common.h"
 
 namespace fk {
@@ -47,16 +52,34 @@ union B128 {
     bf16x8_t v;
 };
 
-// LDS: Wt [H][F + kWPad] bf16 | b1 [H] f32 | w2 [H] f32
-template <int D, int NT>
+static constexpr int kFeatPlanes = 6;
+static constexpr float kFeatDecay = 0.9f;  // Appendix B.1: decay of the carried attention sum per chunk
+
+// geometry of the feature part for group size GF (0: no features)
+template <int D, int GF> struct ScoreCfg {
+    static constexpr int A = kFeatPlanes * GF;       // attention features per pair
+    static constexpr int KA = (A + 15) / 16;         // their k-steps of 16 (zero padded)
+    static constexpr int F = 2 * D + A;              // rows of W1
+    static constexpr int FP = 2 * D + 16 * KA;       // features after padding
+    static constexpr int FS = FP + kWPad;            // LDS row stride in bf16 elements
+    static constexpr int GP = GF <= 4 ? 4 : 8;       // heads per slot in the feature state
+};
+
+__device__ __forceinline__ uint32_t bf16_rn(float x) { return (__float_as_uint(x) + 0x7fffu + ((__float_as_uint(x) >> 16) & 1u)) >> 16; }
+
+// LDS: Wt [H][FS] bf16 | b1 [H] f32 | w2 [H] f32
+template <int D, int NT, int GF>
 __global__ __launch_bounds__(kScoreThreads) void score_mfma_kernel(
-    const bf16_t* __restrict__ K, const bf16_t* __restrict__ V, const int32_t* __restrict__ len,
+    const bf16_t* __restrict__ K, const bf16_t* __restrict__ V, const float* __restrict__ feat,
+    const int32_t* __restrict__ len,
     const bf16_t* __restrict__ W1, const float* __restrict__ b1, const float* __restrict__ W2,
     const float* __restrict__ b2, int H, int per_head, int n_kv, int cap, int pairs_per_block,
     float* __restrict__ scores) {
-    constexpr int F = 2 * D;
-    constexpr int FS = F + kWPad;  // LDS row stride in bf16 elements
-    constexpr int KS = F / 16;     // k-steps of 16 features
+    using SC = ScoreCfg<D, GF>;
+    constexpr int F = SC::F;
+    constexpr int FS = SC::FS;     // LDS row stride in bf16 elements
+    constexpr int KS = 2 * D / 16; // k-steps of 16 features over k and v
+    constexpr int KA = SC::KA;
     const int row = blockIdx.y;
     const int hkv = row % n_kv;
     const int n = min(len[row], cap);
@@ -90,6 +113,11 @@ __global__ __launch_bounds__(kScoreThreads) void score_mfma_kernel(
                 dst[((size_t)(jc * 8 + 2 * e + 1) * FS + 2 * fp) / 2] = hi;
             }
         }
+        if constexpr (SC::FP > F) {  // zero the padding features (dwords: F is even)
+            constexpr int padw = (SC::FP - F) / 2;
+            for (int t = threadIdx.x; t < H * padw; t += kScoreThreads)
+                reinterpret_cast<uint32_t*>(s_wt)[((size_t)(t / padw) * FS + F) / 2 + t % padw] = 0u;
+        }
         for (int j = threadIdx.x; j < H; j += kScoreThreads) {
             s_b1[j] = b1[(size_t)hw * H + j];
             s_w2[j] = W2[(size_t)hw * H + j];
@@ -117,6 +145,48 @@ __global__ __launch_bounds__(kScoreThreads) void score_mfma_kernel(
                 xk[t][ks].u = *reinterpret_cast<const uint4*>(src);
             }
         }
+        // attention features of the pair as two bf16 operands (head and remainder); feature
+        // a = head * 6 + plane; the carried planes already include this chunk (cum + wL, 0.9 dec + wL)
+        B128 xh[NT][KA > 0 ? KA : 1], xl[NT][KA > 0 ? KA : 1];
+        if constexpr (GF > 0) {
+            constexpr int GP = SC::GP;
+            const float* frow = feat + (size_t)row * kFeatPlanes * cap * GP;
+#pragma unroll
+            for (int t = 0; t < NT; ++t) {
+                const int p = min(base + t * 32 + l32, p_end - 1);
+                float fv[GP][kFeatPlanes];
+#pragma unroll
+                for (int pl = 0; pl < kFeatPlanes; ++pl)
+#pragma unroll
+                    for (int q4 = 0; q4 < GP / 4; ++q4) {
+                        const float4 v = *reinterpret_cast<const float4*>(frow + ((size_t)pl * cap + p) * GP + q4 * 4);
+                        fv[q4 * 4 + 0][pl] = v.x;
+                        fv[q4 * 4 + 1][pl] = v.y;
+                        fv[q4 * 4 + 2][pl] = v.z;
+                        fv[q4 * 4 + 3][pl] = v.w;
+                    }
+#pragma unroll
+                for (int h = 0; h < GP; ++h) {
+                    fv[h][4] = fv[h][4] + fv[h][3];
+                    fv[h][5] = fmaf(kFeatDecay, fv[h][5], fv[h][3]);
+                }
+#pragma unroll
+                for (int ka = 0; ka < KA; ++ka) {
+                    uint32_t hi[8], lo[8];
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) {
+                        const int a0 = ka * 16 + e, a1 = ka * 16 + 8 + e;  // this lane's feature: a0 (half 0) or a1 (half 1)
+                        const float v0 = a0 < SC::A ? fv[a0 / kFeatPlanes][a0 % kFeatPlanes] : 0.f;
+                        const float v1 = a1 < SC::A ? fv[a1 / kFeatPlanes][a1 % kFeatPlanes] : 0.f;
+                        const float x = half ? v1 : v0;
+                        hi[e] = bf16_rn(x);
+                        lo[e] = bf16_rn(x - __uint_as_float(hi[e] << 16));
+                    }
+                    xh[t][ka].u = make_uint4(hi[0] | (hi[1] << 16), hi[2] | (hi[3] << 16), hi[4] | (hi[5] << 16), hi[6] | (hi[7] << 16));
+                    xl[t][ka].u = make_uint4(lo[0] | (lo[1] << 16), lo[2] | (lo[3] << 16), lo[4] | (lo[5] << 16), lo[6] | (lo[7] << 16));
+                }
+            }
+        }
         float phi[NT];
 #pragma unroll
         for (int t = 0; t < NT; ++t) phi[t] = 0.f;
@@ -135,6 +205,18 @@ __global__ __launch_bounds__(kScoreThreads) void score_mfma_kernel(
 #pragma unroll
                 for (int t = 0; t < NT; ++t)
                     acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a.v, xk[t][ks].v, acc[t], 0, 0, 0);
+            }
+            if constexpr (GF > 0) {
+#pragma unroll
+                for (int ka = 0; ka < KA; ++ka) {
+                    B128 a;
+                    a.u = *reinterpret_cast<const uint4*>(wrow + (KS + ka) * 16);
+#pragma unroll
+                    for (int t = 0; t < NT; ++t) {
+                        acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a.v, xh[t][ka].v, acc[t], 0, 0, 0);
+                        acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a.v, xl[t][ka].v, acc[t], 0, 0, 0);
+                    }
+                }
             }
             // C layout: element i of a lane is hidden unit ht*32 + (i/4)*8 + half*4 + i%4
 #pragma unroll
@@ -213,14 +295,18 @@ __global__ __launch_bounds__(128) void score_simple_kernel(const T* __restrict__
     scores[(size_t)row * cap + p] = phi + b2[hw];
 }
 
-static size_t score_lds_bytes(int D, int H) { return (size_t)H * (2 * D + kWPad) * 2 + (size_t)H * 8; }
+// LDS of the MFMA kernel for group size gf of the feature part (0: no features)
+static size_t score_lds_bytes(int D, int H, int gf = 0) {
+    const int fp = 2 * D + (kFeatPlanes * gf + 15) / 16 * 16;
+    return (size_t)H * (fp + kWPad) * 2 + (size_t)H * 8;
+}
 
-template <int D>
-static fk_status score_mfma_launch(const fk_cache_desc* d, const void* K, const void* V, const int32_t* len,
-                                   int max_len, const fk_scorer* sc, float* scores, hipStream_t st) {
+template <int D, int GF>
+static fk_status score_mfma_launch(const fk_cache_desc* d, const void* K, const void* V, const float* feat,
+                                   const int32_t* len, int max_len, const fk_scorer* sc, float* scores, hipStream_t st) {
     constexpr int NT = 1;
     const int rows = d->batch * d->n_kv_heads;
-    const size_t lds = score_lds_bytes(D, sc->hidden);
+    const size_t lds = score_lds_bytes(D, sc->hidden, GF);
     // pairs per workgroup: fill the chip about once, in whole wave tiles
     const int tile = 32 * NT;  // the waves of a workgroup take tiles round robin
     int chunks = (256 + rows - 1) / rows;
@@ -228,11 +314,11 @@ static fk_status score_mfma_launch(const fk_cache_desc* d, const void* K, const 
     int ppb = (max_len + chunks - 1) / chunks;
     ppb = (ppb + tile - 1) / tile * tile;
     chunks = (max_len + ppb - 1) / ppb;
-    auto kern = score_mfma_kernel<D, NT>;
+    auto kern = score_mfma_kernel<D, NT, GF>;
     if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
         return FK_ERR_LAUNCH;
     hipLaunchKernelGGL(kern, dim3(chunks, rows), dim3(kScoreThreads), lds, st, (const bf16_t*)K,
-                       (const bf16_t*)V, len, (const bf16_t*)sc->w1, sc->b1, sc->w2, sc->b2, sc->hidden,
+                       (const bf16_t*)V, feat, len, (const bf16_t*)sc->w1, sc->b1, sc->w2, sc->b2, sc->hidden,
                        sc->per_head, d->n_kv_heads, d->capacity, ppb, scores);
     return launch_status();
 }
@@ -267,6 +353,32 @@ extern "C" fk_status fk_score_kv(const fk_cache_desc* desc, const void* K, const
     }
     const bool mfma_ok = (H % 32 == 0) && score_lds_bytes(D, H) <= 160 * 1024;
     if (!mfma_ok) return FK_ERR_UNSUPPORTED;
-    if (D == 64) return score_mfma_launch<64>(desc, K, V, len, max_len, scorer, scores, st);
-    return score_mfma_launch<128>(desc, K, V, len, max_len, scorer, scores, st);
+    if (D == 64) return score_mfma_launch<64, 0>(desc, K, V, nullptr, len, max_len, scorer, scores, st);
+    return score_mfma_launch<128, 0>(desc, K, V, nullptr, len, max_len, scorer, scores, st);
+}
+
+extern "C" fk_status fk_score_kv_feat(const fk_cache_desc* desc, const void* K, const void* V, const float* feat,
+                                      const int32_t* len, int32_t max_len, const fk_scorer* scorer, float* scores,
+                                      void* stream) {
+    fk_status s = check_desc(desc);
+    if (s != FK_OK) return s;
+    if (!K || !V || !feat || !len || !scorer || !scores) return FK_ERR_INVALID_ARG;
+    if (!scorer->w1 || !scorer->b1 || !scorer->w2 || !scorer->b2 || scorer->hidden <= 0) return FK_ERR_INVALID_ARG;
+    if (max_len <= 0 || max_len > desc->capacity) return FK_ERR_INVALID_ARG;
+    if (!aligned16(K) || !aligned16(V) || !aligned16(scorer->w1) || !aligned16(feat)) return FK_ERR_INVALID_ARG;
+    if (desc->dtype != FK_BF16 || desc->head_dim != 128) return FK_ERR_UNSUPPORTED;
+    const int g = desc->n_q_heads / desc->n_kv_heads, H = scorer->hidden;
+    if (H % 32 != 0 || score_lds_bytes(128, H, g) > 160 * 1024) return FK_ERR_UNSUPPORTED;
+    hipStream_t st = (hipStream_t)stream;
+    switch (g) {
+        case 1: return score_mfma_launch<128, 1>(desc, K, V, feat, len, max_len, scorer, scores, st);
+        case 2: return score_mfma_launch<128, 2>(desc, K, V, feat, len, max_len, scorer, scores, st);
+        case 3: return score_mfma_launch<128, 3>(desc, K, V, feat, len, max_len, scorer, scores, st);
+        case 4: return score_mfma_launch<128, 4>(desc, K, V, feat, len, max_len, scorer, scores, st);
+        case 5: return score_mfma_launch<128, 5>(desc, K, V, feat, len, max_len, scorer, scores, st);
+        case 6: return score_mfma_launch<128, 6>(desc, K, V, feat, len, max_len, scorer, scores, st);
+        case 7: return score_mfma_launch<128, 7>(desc, K, V, feat, len, max_len, scorer, scores, st);
+        case 8: return score_mfma_launch<128, 8>(desc, K, V, feat, len, max_len, scorer, scores, st);
+    }
+    return FK_ERR_UNSUPPORTED;
 }

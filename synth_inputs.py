@@ -28,7 +28,7 @@ _C1 = np.uint64(0xBF58476D1CE4E5B9)
 _C2 = np.uint64(0x94D049BB133111EB)
 
 # tensor ids of the counter streams
-T_Q, T_K, T_V, T_W1, T_B1, T_W2, T_B2, T_FLAG, T_MIXMEAN, T_MIXSEL, T_LEN, T_SCORE, T_GUMBEL = range(13)
+T_Q, T_K, T_V, T_W1, T_B1, T_W2, T_B2, T_FLAG, T_MIXMEAN, T_MIXSEL, T_LEN, T_SCORE, T_GUMBEL, T_W1A = range(14)
 
 BASE_SEED = 2602032030
 
@@ -285,6 +285,16 @@ def gen_scorer(w: Workload, layer: int):
     w2 = normal(w.seed, T_W2, layer, np.arange(Hkv * H)).reshape(Hkv, H) / np.sqrt(H)
     b2 = normal(w.seed, T_B2, layer, np.arange(Hkv)) / np.sqrt(H)
     return (round_to_storage(w1, w.dtype), b1.astype(np.float32), w2.astype(np.float32), b2.astype(np.float32))
+
+
+def gen_scorer_feat(w: Workload, layer: int, gain: float = 8.0):
+    """Scorer weights for inputs with attention features: W1 [Hkv, 2D + 6g, H], whose first 2D rows are
+    gen_scorer's and whose 6g feature rows are ~ N(0, gain^2 / (6g)) (attention sums are small numbers;
+    the gain makes them move the scores); b1, W2, b2 as gen_scorer."""
+    w1, b1, w2, b2 = gen_scorer(w, layer)
+    A, H, Hkv = 6 * w.group, w.hidden, w.n_kv_heads
+    wa = normal(w.seed, T_W1A, layer, np.arange(Hkv * A * H)).reshape(Hkv, A, H) * (gain / np.sqrt(A))
+    return (np.concatenate([w1, round_to_storage(wa, w.dtype)], axis=1), b1, w2, b2)
 
 
 def gen_scores(seed: int, shape, ties: int = 0) -> np.ndarray:
