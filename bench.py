@@ -93,11 +93,11 @@ def len_schedule(w: si.Workload, lens0: np.ndarray, n_steps: int):
     return out, ev
 
 
-def measured_traffic(w: si.Workload, steps: int):
+def measured_traffic(w: si.Workload, steps: int, features: bool = False):
     """HBM bytes per attention launch from the committed rocprofv3 counter summary (FETCH_SIZE and
     WRITE_SIZE runs of this same command, each scaled on a plain copy of known size); None when the
     summary does not cover this workload / step count."""
-    if w.name != "cfg1-qwen3-4b-layer" or steps != w.steps:
+    if w.name != "cfg1-qwen3-4b-layer" or steps != w.steps or features:
         return None
     path = os.path.join(ROOT, "profiles", "attn_kernel_cfg1_hbm_traffic.txt")
     try:
@@ -113,6 +113,13 @@ def attn_bytes(w: si.Workload, lens_row: np.ndarray) -> float:
     """Algorithmic bytes of one attention launch: K and V once per KV head, plus q and out."""
     e = w.elem_bytes
     return float(w.n_kv_heads * lens_row.sum() * w.head_dim * 2 * e + w.batch * w.n_q_heads * w.head_dim * 2 * e)
+
+
+def feat_bytes(w: si.Workload, lens_row: np.ndarray, chunk_pos: int) -> float:
+    """Algorithmic bytes the attention features add to a launch: the chunk plane, and each window plane
+    that is open at this step, is read and written once per (live pair, query head), fp32."""
+    planes = 1 + sum(1 for wnd in (8, 16, 32) if chunk_pos >= w.interval - wnd)
+    return float(w.n_kv_heads * lens_row.sum() * w.group * 4 * 2 * planes)
 
 
 def cpu_baseline(w: si.Workload, threads: int, windows: int = 3):
@@ -153,6 +160,9 @@ def main():
     ap.add_argument("--prompt", type=int, default=None, help="override the prompt length (to start near the steady state)")
     ap.add_argument("--policy", choices=["topk", "sampled"], default="topk",
                     help="eviction action: deterministic top-k (default) or Top-K multinomial over 2L candidates")
+    ap.add_argument("--features", action="store_true",
+                    help="scorer inputs concat(k, v, attention features): the decode step also keeps the attention sums "
+                         "(bf16, head_dim 128 only; the default run scores on k and v alone)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--no-kernel-timing", action="store_true", help="skip the HIP-event pass over the attention launches")
     args = ap.parse_args()
@@ -191,11 +201,13 @@ def main():
     len0 = dev(np.repeat(lens0.astype(np.int32)[:, None], w.n_kv_heads, axis=1))      # one count per row
     dq, dk, dv, dp = dev(qh), dev(kh), dev(vh), dev(ph)
     del Kh, Vh, qh, kh, vh
-    W1, b1, W2, b2 = si.gen_scorer(w, 0)
+    W1, b1, W2, b2 = si.gen_scorer_feat(w, 0) if args.features else si.gen_scorer(w, 0)
     dW = [dev(si.storage_array(W1, w.dtype)), dev(b1), dev(W2), dev(b2)]
     desc = fk.CacheDesc(w.batch, w.n_q_heads, w.n_kv_heads, w.head_dim, w.capacity, w.dtype)
     Kc, Vc, posc, lenc = (torch.empty_like(x) for x in (K0, V0, pos0, len0))
     ws = fk.new_attn_workspace(desc)
+    feat = fk.new_feat(desc) if args.features else None
+    fws = fk.new_feat_workspace(desc) if args.features else None
     out = torch.empty((w.batch, w.n_q_heads, w.head_dim), dtype=desc.torch_dtype, device="cuda")
     scores = torch.zeros((w.batch, w.n_kv_heads, w.capacity), dtype=torch.float32, device="cuda")
     keep = torch.zeros((w.batch, w.n_kv_heads, B), dtype=torch.int32, device="cuda")
@@ -209,22 +221,34 @@ def main():
 
     def reset():
         Kc.copy_(K0); Vc.copy_(V0); posc.copy_(pos0); lenc.copy_(len0)
+        if feat is not None:
+            feat.zero_()
 
     def run(n_steps, ev_pairs=None):
         for t in range(n_steps):
             ml = int(min(max_at[t], w.capacity))
             if ev_pairs is not None and t % L == 0:
                 ev_pairs[t // L][0].record(stream)
-            fk.fk_decode_step(desc, dq[t], Kc, Vc, posc, lenc, dk[t], dv[t], dp[t], ml, scale, out, ws, stream)
+            if feat is None:
+                fk.fk_decode_step(desc, dq[t], Kc, Vc, posc, lenc, dk[t], dv[t], dp[t], ml, scale, out, ws, stream)
+            else:
+                fk.fk_decode_step_feat(desc, dq[t], Kc, Vc, posc, lenc, dk[t], dv[t], dp[t], ml, scale, feat, t % L, L, out,
+                                       fws, stream)
             if ev_pairs is not None and ((t + 1) % L == 0 or t + 1 == n_steps):
                 ev_pairs[t // L][1].record(stream)
             if (t + 1) % L == 0:
-                fk.fk_score_kv(desc, Kc, Vc, lenc, ml, *dW, scores, stream)
+                if feat is None:
+                    fk.fk_score_kv(desc, Kc, Vc, lenc, ml, *dW, scores, stream)
+                else:
+                    fk.fk_score_kv_feat(desc, Kc, Vc, feat, lenc, ml, *dW, scores, stream)
                 if noise_pool is None:
                     fk.fk_select_keep(desc, scores, posc, lenc, ml, B, L, keep, stream)
                 else:
                     fk.fk_select_keep_sampled(desc, scores, noise_pool[(t // L) % 8], posc, lenc, ml, B, L, 2 * L, keep, stream)
-                fk.fk_compact(desc, Kc, Vc, posc, lenc, keep, B, stream)
+                if feat is None:
+                    fk.fk_compact(desc, Kc, Vc, posc, lenc, keep, B, stream)
+                else:
+                    fk.fk_compact_feat(desc, Kc, Vc, posc, feat, lenc, keep, B, stream)
 
     # warm-up (untimed), then restart from the prompt
     reset()
@@ -245,6 +269,8 @@ def main():
 
     tokens_per_s = w.batch * K_steps / wall
     total_attn_bytes = sum(attn_bytes(w, lens_at[t]) for t in range(K_steps))
+    if args.features:
+        total_attn_bytes += sum(feat_bytes(w, lens_at[t], t % L) for t in range(K_steps))
     result = {
         "metric": "decode tokens/s, budgeted KV decode+evict (attention + scorer + top-k + compaction), one layer",
         "value": tokens_per_s, "unit": "tokens/s", "n_gpus": 1, "steps": K_steps, "warmup": W_steps,
@@ -252,7 +278,8 @@ def main():
         "dtype": w.dtype, "data": "synthetic",
         "config": {"workload": w.name, "batch": w.batch, "n_q_heads": w.n_q_heads, "n_kv_heads": w.n_kv_heads,
                    "head_dim": w.head_dim, "prompt": w.prompt, "budget": B, "eviction_interval": L,
-                   "capacity": w.capacity, "scorer_hidden": w.hidden, "eviction_policy": args.policy},
+                   "capacity": w.capacity, "scorer_hidden": w.hidden, "eviction_policy": args.policy,
+                   "scorer_inputs": "k, v, attention features" if args.features else "k, v"},
         "path_gbs_algorithmic": total_attn_bytes / wall / 1e9,
     }
 
@@ -269,9 +296,10 @@ def main():
         ms = np.array([total_ms / K_steps])
         avg_bytes = total_attn_bytes / K_steps
         achieved = avg_bytes / (ms.mean() * 1e-3) / 1e9
-        result["roofline"] = {"kernel": "attn_kernel (fk_decode_step: append + split-K attention + merge, one launch)", "bound": "hbm", "achieved": achieved,
+        result["roofline"] = {"kernel": "attn_kernel (fk_decode_step_feat: append + attention + attention-feature update, one launch)" if args.features
+                              else "attn_kernel (fk_decode_step: append + split-K attention + merge, one launch)", "bound": "hbm", "achieved": achieved,
                               "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
-                              "traffic": measured_traffic(w, K_steps),
+                              "traffic": measured_traffic(w, K_steps, args.features),
                               "avg_launch_us": float(ms.mean() * 1e3), "algorithmic_bytes_per_launch": avg_bytes}
     if "roofline" in result:
         # achievable streaming-read bandwidth on this machine, beside the nominal peak: the K cache of this
@@ -291,7 +319,7 @@ def main():
             return t.numel() * t.element_size() * iters / (e0.elapsed_time(e1) * 1e-3) / 1e9
         result["roofline"]["stream_read_gbs"] = {"k_cache": stream_gbs(Kc, 50), "buffer_4gib": stream_gbs(big, 10)}
         del big
-    if not args.no_cpu:
+    if not args.no_cpu and not args.features:   # the oracle's protocol loop covers the default path
         result["cpu_baseline"] = cpu_baseline(w, host_threads)
     print(json.dumps(result), flush=True)
 

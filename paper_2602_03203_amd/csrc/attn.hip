@@ -641,27 +641,46 @@ __global__ __launch_bounds__((AttnCfg<T, D, G>::THREADS)) void attn_kernel(const
         const bool on8 = P.chunk_pos >= P.chunk_len - 8, on16 = P.chunk_pos >= P.chunk_len - 16,
                    on32 = P.chunk_pos >= P.chunk_len - 32;
         const float4 zero = make_float4(0.f, 0.f, 0.f, 0.f);
-        for (int t = tid; t < n * Q4; t += C::THREADS) {
-            const int i = t / Q4, h0 = (t % Q4) * 4;
-            const float4 s = *reinterpret_cast<const float4*>(lg_row + (size_t)i * GP + h0);
-            float4 p;
-            p.x = h0 + 0 < G ? exp2f(s.x - s_M[h0 + 0]) * s_invL[h0 + 0] : 0.f;
-            p.y = h0 + 1 < G ? exp2f(s.y - s_M[h0 + 1]) * s_invL[h0 + 1] : 0.f;
-            p.z = h0 + 2 < G ? exp2f(s.z - s_M[h0 + 2]) * s_invL[h0 + 2] : 0.f;
-            p.w = h0 + 3 < G ? exp2f(s.w - s_M[h0 + 3]) * s_invL[h0 + 3] : 0.f;
-            float4* f = reinterpret_cast<float4*>(frow + (size_t)i * GP + h0);
-            if (i == new_slot) {
-                f[FEAT_W8 * pl4] = keep_if(on8, p);
-                f[FEAT_W16 * pl4] = keep_if(on16, p);
-                f[FEAT_W32 * pl4] = keep_if(on32, p);
-                f[FEAT_WL * pl4] = p;
-                f[FEAT_CUM * pl4] = zero;
-                f[FEAT_DEC * pl4] = zero;
-            } else {
-                feat_add(f + FEAT_WL * pl4, p);
-                if (on32) feat_add(f + FEAT_W32 * pl4, p);
-                if (on16) feat_add(f + FEAT_W16 * pl4, p);
-                if (on8) feat_add(f + FEAT_W8 * pl4, p);
+        // four units (slot, 4 heads) per thread and pass, all loads issued before the first use
+        constexpr int U = 4;
+        const int units = n * Q4;
+        const int h0 = (tid % Q4) * 4;  // THREADS is a multiple of Q4: a thread keeps its head quad
+        float4 mq, iq;                  // maxima and 1 / normalisers of this thread's heads
+        mq.x = h0 + 0 < G ? s_M[h0 + 0] : 0.f;  iq.x = h0 + 0 < G ? s_invL[h0 + 0] : 0.f;
+        mq.y = h0 + 1 < G ? s_M[h0 + 1] : 0.f;  iq.y = h0 + 1 < G ? s_invL[h0 + 1] : 0.f;
+        mq.z = h0 + 2 < G ? s_M[h0 + 2] : 0.f;  iq.z = h0 + 2 < G ? s_invL[h0 + 2] : 0.f;
+        mq.w = h0 + 3 < G ? s_M[h0 + 3] : 0.f;  iq.w = h0 + 3 < G ? s_invL[h0 + 3] : 0.f;
+        const float4* lg4 = reinterpret_cast<const float4*>(lg_row);
+        float4* f4 = reinterpret_cast<float4*>(frow);
+        for (int t0 = tid; t0 < units; t0 += C::THREADS * U) {
+            float4 s[U], w[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int t = min(t0 + u * C::THREADS, units - 1);
+                s[u] = lg4[t];
+                w[u] = f4[FEAT_WL * pl4 + t];
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int t = t0 + u * C::THREADS;
+                if (t >= units) break;
+                // padded heads: their logits are 0 and iq is 0, so p = 0
+                const float4 p = make_float4(exp2f(s[u].x - mq.x) * iq.x, exp2f(s[u].y - mq.y) * iq.y,
+                                             exp2f(s[u].z - mq.z) * iq.z, exp2f(s[u].w - mq.w) * iq.w);
+                float4* f = f4 + t;
+                if (t / Q4 == new_slot) {
+                    f[FEAT_W8 * pl4] = keep_if(on8, p);
+                    f[FEAT_W16 * pl4] = keep_if(on16, p);
+                    f[FEAT_W32 * pl4] = keep_if(on32, p);
+                    f[FEAT_WL * pl4] = p;
+                    f[FEAT_CUM * pl4] = zero;
+                    f[FEAT_DEC * pl4] = zero;
+                } else {
+                    f[FEAT_WL * pl4] = make_float4(w[u].x + p.x, w[u].y + p.y, w[u].z + p.z, w[u].w + p.w);
+                    if (on32) feat_add(f + FEAT_W32 * pl4, p);
+                    if (on16) feat_add(f + FEAT_W16 * pl4, p);
+                    if (on8) feat_add(f + FEAT_W8 * pl4, p);
+                }
             }
         }
     }
