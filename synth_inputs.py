@@ -28,7 +28,7 @@ _C1 = np.uint64(0xBF58476D1CE4E5B9)
 _C2 = np.uint64(0x94D049BB133111EB)
 
 # tensor ids of the counter streams
-T_Q, T_K, T_V, T_W1, T_B1, T_W2, T_B2, T_FLAG, T_MIXMEAN, T_MIXSEL, T_LEN, T_SCORE, T_GUMBEL, T_W1A = range(14)
+T_Q, T_K, T_V, T_W1, T_B1, T_W2, T_B2, T_FLAG, T_MIXMEAN, T_MIXSEL, T_LEN, T_SCORE, T_GUMBEL, T_W1A, T_ATT, T_ATTKEY = range(16)
 
 BASE_SEED = 2602032030
 
@@ -318,3 +318,24 @@ def gen_gumbel(seed: int, shape, event: int = 0, levels: int = 0) -> np.ndarray:
     if levels > 0:
         g = np.round(g * levels / 4.0) * (4.0 / levels)
     return g.astype(np.float32)
+
+
+def gen_attention(seed: int, n_heads: int, T: int, dtype: str = "f32", spread: float = 1.5, sinks: int = 4,
+                  heavy_frac: float = 0.02, recency: float = 96.0) -> np.ndarray:
+    """Synthetic causal attention matrices [n_heads, T, T] of a full trace, float32 values rounded to the
+    storage type: row-wise softmax of random logits with the structure reasoning traces show (a few sink
+    positions, sparse heavy keys whose weight comes and goes per query, a recency ramp); zero above the
+    diagonal.  Stands in for the attention of a real model on a real trace."""
+    A = np.zeros((n_heads, T, T), np.float32)
+    key_u = uniform01(seed, T_ATTKEY, 0, np.arange(n_heads * T)).reshape(n_heads, T)
+    key_bias = np.where(key_u < heavy_frac, 3.0, 0.0)
+    key_bias[:, :sinks] += 4.0
+    dist = np.arange(T)[:, None] - np.arange(T)[None, :]              # q - i
+    ramp = -np.minimum(np.maximum(dist, 0), 4 * recency) / recency
+    for h in range(n_heads):
+        z = spread * normal(seed, T_ATT, h, np.arange(T * T)).reshape(T, T) + key_bias[h][None, :] + ramp
+        z = np.where(dist >= 0, z, -np.inf)
+        z -= z.max(axis=1, keepdims=True)
+        e = np.exp(z)
+        A[h] = (e / e.sum(axis=1, keepdims=True)).astype(np.float32)
+    return round_to_storage(A, dtype)
