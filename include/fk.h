@@ -215,6 +215,41 @@ fk_status fk_compact_feat(const fk_cache_desc *desc, void *K, void *V, int32_t *
                           int32_t *len, const int32_t *keep_idx, int32_t budget, void *stream);
 
 /*
+ * ---- Golden Eviction label builder (Section 3.2 Eq. 3-5; training-side, outside the decode loop) ----
+ *
+ * Input: the attention matrices of the query heads of one layer on a full trace of T tokens,
+ *   A [n_q_heads][T][ld] dtype (fp32 or bf16), row = query position, column = key position (0-based),
+ *   ld >= T elements per row with ld % 8 == 0; precondition A[h][q][i] == 0 for i > q (causal).
+ * With budget B and eviction length L (L <= B) the queries from B + L on form M = ceil((T - B)/L) - 1
+ * blocks; block t = 1 .. M holds queries B + tL .. min(B + (t+1)L, T) - 1, the last one counted as L
+ * queries (zero padded).
+ */
+
+/* M for a trace of T tokens; -1 on bad arguments. */
+int32_t fk_golden_steps(int32_t T, int32_t budget, int32_t interval);
+
+/*
+ * Eq. 3-4 and the first half of Eq. 5:
+ *   block_scores[h'][t-1][i] = 1/(g L) sum_{h in group h'} sum_{q in block t} A[h][q][i]     (average pooling)
+ *   alpha[h'][t-1][i]        = max_{t <= j <= M} block_scores[h'][j-1][i]                    (future score)
+ * both [n_kv_heads][M][T] fp32, fp32 accumulation; nothing is written when M == 0.
+ */
+fk_status fk_golden_scores(const void *A, int32_t dtype, int32_t n_q_heads, int32_t n_kv_heads, int32_t T,
+                           int64_t ld, int32_t budget, int32_t interval, float *block_scores,
+                           float *alpha, void *stream);
+
+/*
+ * Second half of Eq. 5 as an eviction trace under the protocol of Section 3.1: before step 1 the cache
+ * holds positions 0 .. B + L - 1; step t keeps the L newest (B + tL - L .. B + tL - 1) and, of the other B
+ * it holds, the B - L with the largest alpha[h'][t-1][.] (ties: the lower position); then positions
+ * B + tL .. B + (t+1)L - 1 join.  kept [n_kv_heads][M][B] int32: the positions retained after step t,
+ * ascending.  -0 equals +0 and NaN ranks lowest, as in fk_select_keep.  B + L <= 12288
+ * (FK_ERR_UNSUPPORTED above).
+ */
+fk_status fk_golden_trace(const float *alpha, int32_t n_kv_heads, int32_t T, int32_t budget,
+                          int32_t interval, int32_t *kept, void *stream);
+
+/*
  * Measurement helper, not part of the method: reads `bytes` (>= 16) of device memory at `src` with
  * 16-byte loads and discards them; `sink` is 4 bytes of device memory.  bench.py times it to report
  * the achievable streaming bandwidth of the box beside the nominal HBM peak.

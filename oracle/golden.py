@@ -30,17 +30,18 @@ def n_steps(T: int, B: int, L: int) -> int:
 
 
 def block_scores(A: np.ndarray, g: int, B: int, L: int) -> np.ndarray:
-    """Eq. 3 and 4.  A float64 [Hq, T, T]; returns a~ [Hq / g, M, T] (index t - 1 along the block axis)."""
-    Hq, T, T2 = A.shape
-    assert T == T2 and Hq % g == 0 and A.dtype == np.float64
+    """Eq. 3 and 4.  A float64 [Hq, T, C] with C = T, or any subset of the key columns (columns do not
+    interact); returns a~ [Hq / g, M, C] (index t - 1 along the block axis)."""
+    Hq, T, C = A.shape
+    assert Hq % g == 0 and A.dtype == np.float64
     M = n_steps(T, B, L)
-    out = np.zeros((Hq // g, M, T), np.float64)
+    out = np.zeros((Hq // g, M, C), np.float64)
     for t in range(1, M + 1):
         q0, q1 = B + t * L, min(B + (t + 1) * L, T)
         for hp in range(Hq // g):
-            acc = np.zeros(T, np.float64)
+            acc = np.zeros(C, np.float64)
             for h in range(hp * g, (hp + 1) * g):
-                a_h = np.zeros(T, np.float64)
+                a_h = np.zeros(C, np.float64)
                 for q in range(q0, q1):
                     a_h += A[h, q]
                 acc += a_h / L              # Eq. 3: average over the L (zero padded) query rows

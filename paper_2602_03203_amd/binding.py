@@ -21,7 +21,8 @@ FK_F32, FK_BF16 = 0, 1
 
 SYMBOLS = ["fk_status_string", "fk_version", "fk_append", "fk_decode_attn_workspace", "fk_decode_attn", "fk_decode_step",
            "fk_score_kv", "fk_select_keep", "fk_select_keep_sampled", "fk_compact", "fk_decode_step_feat_workspace",
-           "fk_decode_step_feat", "fk_score_kv_feat", "fk_compact_feat", "fk_stream_read"]
+           "fk_decode_step_feat", "fk_score_kv_feat", "fk_compact_feat", "fk_golden_steps", "fk_golden_scores",
+           "fk_golden_trace", "fk_stream_read"]
 
 
 class fk_cache_desc(ctypes.Structure):
@@ -66,6 +67,9 @@ def lib() -> ctypes.CDLL:
         L.fk_decode_step_feat.restype, L.fk_decode_step_feat.argtypes = ctypes.c_int, [dp, vp, vp, vp, vp, vp, vp, vp, vp, i32, f32, vp, i32, i32, vp, vp, sz, vp]
         L.fk_score_kv_feat.restype, L.fk_score_kv_feat.argtypes = ctypes.c_int, [dp, vp, vp, vp, vp, i32, sp, vp, vp]
         L.fk_compact_feat.restype, L.fk_compact_feat.argtypes = ctypes.c_int, [dp, vp, vp, vp, vp, vp, vp, i32, vp]
+        L.fk_golden_steps.restype, L.fk_golden_steps.argtypes = i32, [i32, i32, i32]
+        L.fk_golden_scores.restype, L.fk_golden_scores.argtypes = ctypes.c_int, [vp, i32, i32, i32, i32, ctypes.c_int64, i32, i32, vp, vp, vp]
+        L.fk_golden_trace.restype, L.fk_golden_trace.argtypes = ctypes.c_int, [vp, i32, i32, i32, i32, vp, vp]
         L.fk_stream_read.restype, L.fk_stream_read.argtypes = ctypes.c_int, [vp, sz, vp, vp]
         _lib = L
     return _lib
@@ -206,6 +210,23 @@ def fk_score_kv_feat(desc: CacheDesc, K, V, feat, length, max_len: int, W1, b1, 
 def fk_compact_feat(desc: CacheDesc, K, V, pos, feat, length, keep_idx, budget: int, stream=None) -> None:
     _check(lib().fk_compact_feat(ctypes.byref(desc.c()), _ptr(K), _ptr(V), _ptr(pos), _ptr(feat), _ptr(length),
                                  _ptr(keep_idx), int(budget), _stream(stream)), "fk_compact_feat")
+
+
+def fk_golden_steps(T: int, budget: int, interval: int) -> int:
+    return int(lib().fk_golden_steps(int(T), int(budget), int(interval)))
+
+
+def fk_golden_scores(A, n_kv_heads: int, T: int, budget: int, interval: int, block_scores, alpha, stream=None) -> None:
+    """A [n_q_heads, T, ld] fp32 or bf16 (ld = A.shape[2] >= T); block_scores, alpha [n_kv_heads, M, T] fp32."""
+    _check(lib().fk_golden_scores(_ptr(A), FK_F32 if A.dtype == torch.float32 else FK_BF16, int(A.shape[0]), int(n_kv_heads),
+                                  int(T), int(A.shape[2]), int(budget), int(interval), _ptr(block_scores), _ptr(alpha),
+                                  _stream(stream)), "fk_golden_scores")
+
+
+def fk_golden_trace(alpha, T: int, budget: int, interval: int, kept, stream=None) -> None:
+    """alpha [n_kv_heads, M, T] fp32; kept [n_kv_heads, M, budget] int32."""
+    _check(lib().fk_golden_trace(_ptr(alpha), int(alpha.shape[0]), int(T), int(budget), int(interval), _ptr(kept),
+                                 _stream(stream)), "fk_golden_trace")
 
 
 def fk_stream_read(src, sink, stream=None) -> None:
