@@ -109,6 +109,17 @@ def measured_traffic(w: si.Workload, steps: int, features: bool = False):
     return None
 
 
+def profile_value(fname: str, key: str):
+    """A `key = number` line of a committed profile summary, or None."""
+    try:
+        for line in open(os.path.join(ROOT, "profiles", fname)):
+            if line.startswith(key):
+                return float(line.split("=")[1])
+    except OSError:
+        pass
+    return None
+
+
 def attn_bytes(w: si.Workload, lens_row: np.ndarray) -> float:
     """Algorithmic bytes of one attention launch: K and V once per KV head, plus q and out."""
     e = w.elem_bytes
@@ -151,6 +162,83 @@ def cpu_baseline(w: si.Workload, threads: int, windows: int = 3):
                       f"{windows} windows of {L} decode steps + 1 eviction event each = {n_steps} steps, {dt:.1f}s CPU"}
 
 
+def bench_golden(args):
+    """Golden Eviction label builder (Section 3.2 Eq. 3-5) at the Qwen3-4B layer shape: 32 query / 8 KV
+    heads, one 8192-token trace, B 2048, L 128, bf16 attention (4.3 GB, HBM resident).  A step = block
+    pooling + future scores + the 47-step eviction trace."""
+    import torch
+    import paper_2602_03203_amd as fk
+    fk.lib()
+    torch.cuda.set_device(0)
+    Hq, Hkv, T, B, L = 32, 8, 8192, 2048, 128
+    g = Hq // Hkv
+    M = fk.fk_golden_steps(T, B, L)
+    K_steps = args.steps if args.steps is not None else 20
+    W_steps = min(args.warmup, 5)
+    gen = torch.Generator(device="cuda").manual_seed(2602)
+    A = torch.empty((Hq, T, T), dtype=torch.bfloat16, device="cuda")
+    causal = torch.ones((T, T), dtype=torch.bool, device="cuda").tril_()
+    for h in range(Hq):
+        z = 1.5 * torch.randn((T, T), generator=gen, device="cuda")
+        z.masked_fill_(~causal, float("-inf"))
+        A[h] = torch.softmax(z, dim=1).to(torch.bfloat16)
+    del z, causal
+    a_t = torch.empty((Hkv, M, T), dtype=torch.float32, device="cuda")
+    alpha = torch.empty_like(a_t)
+    kept = torch.empty((Hkv, M, B), dtype=torch.int32, device="cuda")
+    stream = torch.cuda.current_stream()
+
+    def step():
+        fk.fk_golden_scores(A, Hkv, T, B, L, a_t, alpha, stream)
+        fk.fk_golden_trace(alpha, T, B, L, kept, stream)
+
+    for _ in range(W_steps):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(K_steps):
+        step()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    entries = Hq * sum(q + 1 for q in range(B + L, T))          # causal entries of the pooled queries
+    e0 = [torch.cuda.Event(enable_timing=True) for _ in range(K_steps)]
+    e1 = [torch.cuda.Event(enable_timing=True) for _ in range(K_steps)]
+    for i in range(K_steps):
+        e0[i].record(stream)
+        fk.fk_golden_scores(A, Hkv, T, B, L, a_t, alpha, stream)
+        e1[i].record(stream)
+        fk.fk_golden_trace(alpha, T, B, L, kept, stream)
+    torch.cuda.synchronize()
+    ms = float(np.mean([a.elapsed_time(b) for a, b in zip(e0, e1)]))
+    bytes_alg = entries * 2 + 2 * Hkv * M * T * 4 * 2           # A once; block scores written, read, future scores written
+    achieved = bytes_alg / (ms * 1e-3) / 1e9
+    result = {
+        "metric": "Golden Eviction label builder: causal attention entries pooled per second (pooling + future scores + trace), one layer",
+        "value": entries * K_steps / wall, "unit": "entries/s", "n_gpus": 1, "steps": K_steps, "warmup": W_steps,
+        "ms_per_step": 1e3 * wall / K_steps, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "golden-qwen3-4b-layer-8k", "n_q_heads": Hq, "n_kv_heads": Hkv, "trace_tokens": T, "budget": B,
+                   "eviction_interval": L, "steps_M": M},
+        "roofline": {"kernel": "golden_pool_kernel + golden_future_kernel (fk_golden_scores)", "bound": "hbm", "achieved": achieved,
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
+                     "traffic": profile_value("golden_pool_kernel_qwen3_4b_8k_trace.txt", "traffic_bytes_per_launch"),
+                     "avg_launch_us": ms * 1e3, "algorithmic_bytes_per_launch": bytes_alg},
+    }
+    if not args.no_cpu:
+        from oracle import golden
+        ncol = 2048
+        cols = torch.arange(0, T, T // ncol, device="cuda")
+        sub = A[:, :, cols].float().cpu().numpy().astype(np.float64)
+        t0 = time.perf_counter()
+        a_ref = golden.block_scores(sub, g, B, L)
+        golden.future_scores(a_ref)
+        dt = time.perf_counter() - t0
+        frac = sum(int((cols.cpu().numpy() <= q).sum()) for q in range(B + L, T)) * Hq
+        result["cpu_baseline"] = {"value": frac / dt, "unit": "entries/s", "cores": 1, "kind": "oracle",
+                                  "sample": f"{ncol} of {T} key columns, all heads and blocks, pooling + future scores, {dt:.1f}s CPU"}
+    print(json.dumps(result), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -163,12 +251,16 @@ def main():
     ap.add_argument("--features", action="store_true",
                     help="scorer inputs concat(k, v, attention features): the decode step also keeps the attention sums "
                          "(bf16, head_dim 128 only; the default run scores on k and v alone)")
+    ap.add_argument("--workload", choices=["decode", "golden"], default="decode",
+                    help="decode: the budgeted decode + evict path (the headline); golden: the Golden Eviction label builder")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--no-kernel-timing", action="store_true", help="skip the HIP-event pass over the attention launches")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on ONE GPU (rows are independent; see DESIGN.md for how it would shard); use --gpus 1")
 
+    if args.workload == "golden":
+        return bench_golden(args)
     import torch
     import paper_2602_03203_amd as fk
     fk.lib()  # fail loudly if the HIP library is missing

@@ -69,16 +69,24 @@ __global__ __launch_bounds__(kPoolThreads) void golden_pool_kernel(const T* __re
     }
 }
 
-// alpha[t] = max(a~[t], alpha[t + 1]), walking the blocks from the last to the first; one thread per key
+// alpha[t] = max(a~[t], alpha[t + 1]), walking the blocks from the last to the first; one thread per key,
+// eight blocks' loads in flight
 __global__ void golden_future_kernel(const float* __restrict__ a_tilde, int Tn, int M, float* __restrict__ alpha) {
     const int i = blockIdx.x * blockDim.x + threadIdx.x, hp = blockIdx.y;
     if (i >= Tn) return;
+    const size_t o0 = (size_t)hp * M * Tn + i;
     float run = 0.f;
-    for (int t = M; t >= 1; --t) {
-        const size_t o = ((size_t)hp * M + (t - 1)) * Tn + i;
-        const float a = a_tilde[o];
-        run = t == M ? a : fmaxf(run, a);
-        alpha[o] = run;
+    for (int t = M; t >= 1; t -= 8) {
+        float a[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) a[u] = t - u >= 1 ? a_tilde[o0 + (size_t)(t - u - 1) * Tn] : 0.f;
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            if (t - u >= 1) {
+                run = t - u == M ? a[u] : fmaxf(run, a[u]);
+                alpha[o0 + (size_t)(t - u - 1) * Tn] = run;
+            }
+        }
     }
 }
 
