@@ -30,11 +30,11 @@ __global__ __launch_bounds__(64) void append_kernel(uint4* __restrict__ K, uint4
 // ---------------------------------------------------------------------------------------
 // compact (stable in-place gather)
 //
-// keep[] is ascending with keep[j] >= j.  A workgroup owns one 32-byte column slice of one
-// tensor of one row (bytes of different slices never alias, so slices are independent) and
-// walks the destination slots in ascending tiles of 2048 slots (budgets up to 2048: one tile,
-// i.e. the whole slice is read, then written): all sources of a tile are loaded into
-// registers, a barrier, then the tile is stored.  A store of tile t lands in slots
+// keep[] is ascending with keep[j] >= j.  A workgroup owns one 128-byte column slice of one
+// tensor of one row (bytes of different slices never alias, so slices are independent; 128
+// bytes = two whole 64-byte memory requests per slot, narrower slices fetch and write partial
+// lines and cost 1.5x the time) and walks the destination slots in ascending tiles of 512
+// slots: all sources of a tile are loaded into registers, a barrier, then the tile is stored.  A store of tile t lands in slots
 // [tT, (t+1)T); a source of any later tile is >= (t+1)T, and every source of tile t or of an
 // earlier tile has already been read, so no live source is overwritten.  Entries with
 // keep[j] == j (the untouched prefix) cost no traffic.
@@ -42,7 +42,7 @@ __global__ __launch_bounds__(64) void append_kernel(uint4* __restrict__ K, uint4
 // ---------------------------------------------------------------------------------------
 static constexpr int kCompactThreads = 1024;
 static constexpr int kCompactU = 4;     // 16-byte loads in flight per thread
-static constexpr int kSliceChunks = 2;  // 16-byte chunks per column slice
+static constexpr int kSliceChunks = 8;  // 16-byte chunks per column slice
 
 __global__ __launch_bounds__(kCompactThreads) void compact_kernel(uint4* __restrict__ K, uint4* __restrict__ V,
                                                                   int32_t* __restrict__ pos,
@@ -107,7 +107,6 @@ __global__ __launch_bounds__(kCompactThreads) void compact_kernel(uint4* __restr
 // j in the same pass (ascending tiles, all sources of a tile read before it is written: the
 // argument of compact_kernel).  One workgroup per row; a thread owns 4 heads of a slot.
 // ---------------------------------------------------------------------------------------
-static constexpr float kFeatDecay = 0.9f;
 
 template <int Q4 /* float4 units per slot */>
 __global__ __launch_bounds__(kCompactThreads) void feat_roll_kernel(float4* __restrict__ feat,

@@ -65,6 +65,10 @@ __device__ __forceinline__ float group_sum(float v) {
     return v;
 }
 
+// attention-feature state (Appendix B.1): six planes per (slot, query head); the carried sum decays by 0.9 per chunk
+static constexpr int kFeatPlanes = 6;
+static constexpr float kFeatDecay = 0.9f;
+
 // ---- host side --------------------------------------------------------------------------
 inline fk_status check_desc(const fk_cache_desc* d) {
     if (!d) return FK_ERR_INVALID_ARG;

@@ -52,8 +52,6 @@ union B128 {
     bf16x8_t v;
 };
 
-static constexpr int kFeatPlanes = 6;
-static constexpr float kFeatDecay = 0.9f;  // Appendix B.1: decay of the carried attention sum per chunk
 
 // geometry of the feature part for group size GF (0: no features)
 template <int D, int GF> struct ScoreCfg {
