@@ -133,7 +133,7 @@ def feat_bytes(w: si.Workload, lens_row: np.ndarray, chunk_pos: int) -> float:
     return float(w.n_kv_heads * lens_row.sum() * w.group * 4 * 2 * planes)
 
 
-def cpu_baseline(w: si.Workload, threads: int, windows: int = 3):
+def cpu_baseline(w: si.Workload, threads: int, windows: int = 5):
     """Time the CPU oracle, as it stands, on a bounded sample of the same workload: the full batch at
     steady state (cache at budget) for `windows` eviction windows, each L decode steps (append +
     attention) and one eviction event (score + select + compact)."""
@@ -157,9 +157,16 @@ def cpu_baseline(w: si.Workload, threads: int, windows: int = 3):
     oracle.run_protocol(c, lambda t: step_in[t], n_steps, scorer, B, L, w.softmax_scale, method="sort")
     dt = time.perf_counter() - t0
     assert int(c.len[0]) == B
+    # the same loop on ONE core, one window (the cache is back at B after the run above)
+    oracle.set_threads(1)
+    t0 = time.perf_counter()
+    oracle.run_protocol(c, lambda t: step_in[t], L, scorer, B, L, w.softmax_scale, method="sort")
+    dt1 = time.perf_counter() - t0
+    oracle.set_threads(threads)
     return {"value": Bt * n_steps / dt, "unit": "tokens/s", "cores": threads, "kind": "oracle",
             "sample": f"full batch ({Bt} sequences x {w.n_kv_heads} KV heads) at steady state (cache {B}..{B + L}): "
-                      f"{windows} windows of {L} decode steps + 1 eviction event each = {n_steps} steps, {dt:.1f}s CPU"}
+                      f"{windows} windows of {L} decode steps + 1 eviction event each = {n_steps} steps, {dt:.1f}s CPU",
+            "value_1core": Bt * L / dt1, "sample_1core": f"one such window on one core, {dt1:.1f}s CPU"}
 
 
 def bench_golden(args):
@@ -316,6 +323,8 @@ def main():
         if feat is not None:
             feat.zero_()
 
+    ev_kernels = []
+
     def run(n_steps, ev_pairs=None):
         for t in range(n_steps):
             ml = int(min(max_at[t], w.capacity))
@@ -329,18 +338,29 @@ def main():
             if ev_pairs is not None and ((t + 1) % L == 0 or t + 1 == n_steps):
                 ev_pairs[t // L][1].record(stream)
             if (t + 1) % L == 0:
+                kev = None
+                if ev_pairs is not None:   # per-kernel brackets of the event: [start, after score, after select, after compact]
+                    kev = [torch.cuda.Event(enable_timing=True) for _ in range(4)]
+                    ev_kernels.append((t, kev))
+                    kev[0].record(stream)
                 if feat is None:
                     fk.fk_score_kv(desc, Kc, Vc, lenc, ml, *dW, scores, stream)
                 else:
                     fk.fk_score_kv_feat(desc, Kc, Vc, feat, lenc, ml, *dW, scores, stream)
+                if kev:
+                    kev[1].record(stream)
                 if noise_pool is None:
                     fk.fk_select_keep(desc, scores, posc, lenc, ml, B, L, keep, stream)
                 else:
                     fk.fk_select_keep_sampled(desc, scores, noise_pool[(t // L) % 8], posc, lenc, ml, B, L, 2 * L, keep, stream)
+                if kev:
+                    kev[2].record(stream)
                 if feat is None:
                     fk.fk_compact(desc, Kc, Vc, posc, lenc, keep, B, stream)
                 else:
                     fk.fk_compact_feat(desc, Kc, Vc, posc, feat, lenc, keep, B, stream)
+                if kev:
+                    kev[3].record(stream)
 
     # warm-up (untimed), then restart from the prompt
     reset()
@@ -393,6 +413,23 @@ def main():
                               "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
                               "traffic": measured_traffic(w, K_steps, args.features),
                               "avg_launch_us": float(ms.mean() * 1e3), "algorithmic_bytes_per_launch": avg_bytes}
+        # the event kernels, over the events in which every row is over budget (HIP events between the calls)
+        full = [(t, kev) for (t, kev) in ev_kernels if lens_at[t].min() > B]
+        if full:
+            us = [float(np.mean([k[i].elapsed_time(k[i + 1]) for _, k in full])) * 1e3 for i in range(3)]
+            pairs = float(np.mean([lens_at[t].sum() for t, _ in full])) * w.n_kv_heads   # retained pairs scored per event
+            rows_ = w.batch * w.n_kv_heads
+            e = w.elem_bytes
+            sc_bytes = pairs * (2 * w.head_dim * e + 4)
+            sc_flops = pairs * (2.0 * (2 * w.head_dim + (6 * w.group if args.features else 0)) * w.hidden + 4 * w.hidden)
+            sel_bytes = 4 * pairs + rows_ * 4 * B
+            cp_bytes = rows_ * B * (2 * 2 * w.head_dim * e + 8)
+            result["event_kernels"] = {
+                "events_timed": len(full), "pairs_per_event": pairs,
+                "score": {"us": us[0], "algorithmic_gbs": sc_bytes / us[0] / 1e3, "tflops": sc_flops / us[0] / 1e6},
+                "select": {"us": us[1], "algorithmic_gbs": sel_bytes / us[1] / 1e3},
+                "compact": {"us": us[2], "algorithmic_gbs_upper": cp_bytes / us[2] / 1e3,
+                            "note": "bytes if every kept pair moved; includes the length clamp launch"}}
     if "roofline" in result:
         # achievable streaming-read bandwidth on this machine, beside the nominal peak: the K cache of this
         # workload (fits the Infinity Cache at the default shape) and a 4 GiB buffer (HBM resident)
