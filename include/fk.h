@@ -26,7 +26,9 @@
  *     only enqueues work on it and returns; nothing is allocated, no state is kept;
  *   - errors are return codes; arguments are validated on the host before any launch;
  *   - `max_len` is a host-side upper bound on every len[r] at the time the kernels run
- *     (pass `capacity` when unknown); it only sizes the launch.
+ *     (pass `capacity` when unknown); it only sizes the launch.  fk_decode_attn / fk_decode_step stay
+ *     correct when a row is longer than max_len (its last split runs on to the row's end); fk_score_kv
+ *     may leave slots beyond max_len unscored.
  *   - supported: head_dim 64 or 128; dtype fp32 or bf16; n_q_heads a multiple of
  *     n_kv_heads with group size <= 8; capacity < 2^24.
  */

@@ -179,7 +179,8 @@ __global__ __launch_bounds__((AttnCfg<T, D, G>::THREADS)) void attn_kernel(const
     const int n_old = min(max(P.len[row], 0), P.cap);
     const bool do_append = appending && n_old < P.cap;
     const int n = n_old + (do_append ? 1 : 0);
-    const int used = (n + P.split_len - 1) / P.split_len;
+    // splits in use; if the caller's max_len was too small the last split runs on to the row's end (slower, still right)
+    const int used = min((n + P.split_len - 1) / P.split_len, P.nsplit);
     T* out = reinterpret_cast<T*>(P.out) + ((size_t)b * P.n_kv + hkv) * G * D;
 
     // Every workgroup of the row calls finish() once, as its last action.  With one workgroup per
@@ -233,7 +234,7 @@ __global__ __launch_bounds__((AttnCfg<T, D, G>::THREADS)) void attn_kernel(const
         return;
     }
     const int start = split * P.split_len;
-    const int end = min(start + P.split_len, n);
+    const int end = split == used - 1 ? n : start + P.split_len;
 
     T* Kr = reinterpret_cast<T*>(P.K) + (size_t)row * P.cap * D;
     T* Vr = reinterpret_cast<T*>(P.V) + (size_t)row * P.cap * D;

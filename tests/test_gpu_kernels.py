@@ -48,6 +48,10 @@ def test_decode_attn_matches_oracle(gpu, ora, dtype, D, Hq, Hkv, cap, lens):
     # a tighter max_len hint that still covers every row gives the same answer
     got = dev.attn(qd, D ** -0.5, max_len=max(max(lens), 1))
     gpu.assert_attn_close(got, ora.decode_attn(c, q, D ** -0.5), dtype, "max_len hint")
+    # a hint that is too small only costs time: the last split runs on to the end of the row
+    for hint in (1, 33, max(max(lens) // 3, 1)):
+        got = dev.attn(qd, D ** -0.5, max_len=hint)
+        gpu.assert_attn_close(got, ora.decode_attn(c, q, D ** -0.5), dtype, f"max_len hint {hint} below the lengths")
 
 
 def test_decode_attn_closed_forms_on_device(gpu, ora):
