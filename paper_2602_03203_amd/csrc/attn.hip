@@ -204,18 +204,38 @@ __global__ __launch_bounds__((AttnCfg<T, D, G>::THREADS)) void attn_kernel(const
         __syncthreads();
         if (!s_last) return;
         if (used > 1) {
+            // log-sum-exp merge of the splits' records, eight records' loads in flight per thread
             const float* r0 = P.rec + (size_t)row * P.nsplit * G * (D + 2);
             const size_t stride = (size_t)G * (D + 2);
             for (int idx = tid; idx < G * D; idx += C::THREADS) {
                 const int h = idx / D, d = idx % D;
                 const float* r = r0 + (size_t)h * (D + 2);
-                float mn = kNegBig;
-                for (int s = 0; s < used; ++s) mn = fmaxf(mn, ld_agent(r + s * stride + D));
-                float a = 0.f, ls = 0.f;
-                for (int s = 0; s < used; ++s) {
-                    const float cw = exp2f(ld_agent(r + s * stride + D) - mn);
-                    a = fmaf(ld_agent(r + s * stride + d), cw, a);
-                    ls = fmaf(ld_agent(r + s * stride + D + 1), cw, ls);
+                float M = kNegBig, a = 0.f, ls = 0.f;
+                for (int s0 = 0; s0 < used; s0 += 8) {
+                    float mv[8], lv[8], av[8];
+#pragma unroll
+                    for (int u = 0; u < 8; ++u) {
+                        const float* rs = r + (size_t)min(s0 + u, used - 1) * stride;
+                        mv[u] = ld_agent(rs + D);
+                        lv[u] = ld_agent(rs + D + 1);
+                        av[u] = ld_agent(rs + d);
+                    }
+                    float cm = M;
+#pragma unroll
+                    for (int u = 0; u < 8; ++u)
+                        if (s0 + u < used) cm = fmaxf(cm, mv[u]);
+                    const float c0 = exp2f(M - cm);
+                    a *= c0;
+                    ls *= c0;
+                    M = cm;
+#pragma unroll
+                    for (int u = 0; u < 8; ++u) {
+                        if (s0 + u < used) {
+                            const float cw = exp2f(mv[u] - M);
+                            a = fmaf(av[u], cw, a);
+                            ls = fmaf(lv[u], cw, ls);
+                        }
+                    }
                 }
                 store_out(out + idx, a / ls);
             }
