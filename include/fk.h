@@ -168,7 +168,7 @@ fk_status fk_compact(const fk_cache_desc *desc, void *K, void *V, int32_t *pos, 
                      const int32_t *keep_idx, int32_t budget, void *stream);
 
 /*
- * ---- Attention features of the scoring model (Appendix B.1; bf16 with head_dim 128 only) ----
+ * ---- Attention features of the scoring model (Appendix B.1) ----
  *
  * Beside k and v the scorer sees, for every retained pair and every query head of its group, six sums of
  * the attention weights the pair received: over the last 8, 16 and 32 queries of the current chunk of L
@@ -200,8 +200,8 @@ fk_status fk_decode_step_feat(const fk_cache_desc *desc, const void *q, void *K,
 /*
  * fk_score_kv on x = concat(k, v, a) (Section 3.1 Eq. 1 with the attention features of Appendix
  * B.1).  scorer->w1 is [n_sets][2*head_dim + 6 g][hidden]; the fp32 features enter the contraction as
- * a bf16 head plus a bf16 remainder (16 significant bits).  FK_ERR_UNSUPPORTED unless hidden is a
- * multiple of 32 and hidden * (2*head_dim + roundup(6 g, 16) + 8) * 2 + 8 * hidden <= 160 KiB.
+ * a bf16 head plus a bf16 remainder (16 significant bits; fp32 caches: plain fp32).  bf16: FK_ERR_UNSUPPORTED
+ * unless hidden is a multiple of 32 and hidden * (2*head_dim + roundup(6 g, 16) + 8) * 2 + 8 * hidden <= 160 KiB.
  */
 fk_status fk_score_kv_feat(const fk_cache_desc *desc, const void *K, const void *V, const float *feat,
                            const int32_t *len, int32_t max_len, const fk_scorer *scorer, float *scores,

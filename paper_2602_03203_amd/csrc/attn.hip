@@ -85,6 +85,7 @@ template <typename T, int D, int G> struct AttnCfg {
         (PVM ? (size_t)WAVES * KT * KRS : 0);
     // attention-feature variant (PVM only): lx [NG][G] exact normaliser partials | invL [8], behind the K tiles
     static constexpr size_t LDS_BYTES_FEAT = LDS_BYTES + sizeof(float) * ((size_t)NG * G + 8);
+    static constexpr size_t LX_OFFSET = LDS_BYTES / sizeof(float);  // float index of lx in the dynamic LDS
 };
 
 struct AttnPlan {
@@ -159,7 +160,6 @@ __device__ __forceinline__ float4 keep_if(bool c, const float4 p) {
 template <typename T, int D, int G, bool FEAT>
 __global__ __launch_bounds__((AttnCfg<T, D, G>::THREADS)) void attn_kernel(const AttnParams P) {
     using C = AttnCfg<T, D, G>;
-    static_assert(!FEAT || C::PVM, "the feature variant exists for bf16, D = 128 only");
     constexpr int CH = C::CH, KG = C::KG, WAVES = C::WAVES, KT = C::KT, VU = C::VU, EPL = C::EPL, GP = C::GP, NG = C::NG;
     const int row = blockIdx.y, split = blockIdx.x;
     const int b = row / P.n_kv, hkv = row % P.n_kv;
@@ -415,8 +415,7 @@ __global__ __launch_bounds__((AttnCfg<T, D, G>::THREADS)) void attn_kernel(const
             }
             if constexpr (FEAT) {
                 const float lxs = group_sum<16>(lx_run[i]);
-                float* s_lx = reinterpret_cast<float*>(reinterpret_cast<unsigned char*>(s_corr + WAVES * GP + 4) + (size_t)WAVES * KT * KRS);
-                if (h < G && n16 == 0) s_lx[wave * G + h] = lxs;
+                if (h < G && n16 == 0) smem[C::LX_OFFSET + wave * G + h] = lxs;
             }
         }
     } else if constexpr (C::MFMA) {
@@ -460,6 +459,17 @@ __global__ __launch_bounds__((AttnCfg<T, D, G>::THREADS)) void attn_kernel(const
                     c[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(qa[ks].v, kb[nt][ks].v, c[nt], 0, 0, 0);
             }
             // result layout: lane = key n16 of tile nt, element i = head quad*4 + i
+            if constexpr (FEAT) {
+                float* lg_row = P.logit + (size_t)row * P.cap * GP;
+                if (quad * 4 < GP) {
+                    if (base + n16 < end)
+                        *reinterpret_cast<float4*>(lg_row + (size_t)(base + n16) * GP + quad * 4) =
+                            make_float4(c[0][0] * P.scale_log2e, c[0][1] * P.scale_log2e, c[0][2] * P.scale_log2e, c[0][3] * P.scale_log2e);
+                    if (base + 16 + n16 < end)
+                        *reinterpret_cast<float4*>(lg_row + (size_t)(base + 16 + n16) * GP + quad * 4) =
+                            make_float4(c[1][0] * P.scale_log2e, c[1][1] * P.scale_log2e, c[1][2] * P.scale_log2e, c[1][3] * P.scale_log2e);
+                }
+            }
             float p[2][4], corr[4];
             bool changed = false;
 #pragma unroll
@@ -562,6 +572,16 @@ __global__ __launch_bounds__((AttnCfg<T, D, G>::THREADS)) void attn_kernel(const
                     d = group_sum<CH>(d);
                     s[u][h] = key[u] < end ? d : kNegBig;
                 }
+                if constexpr (FEAT) {
+                    if (dl == 0 && key[u] < end) {  // heads beyond the group hold zeros
+                        float* lg = P.logit + ((size_t)row * P.cap + key[u]) * GP;
+#pragma unroll
+                        for (int h4 = 0; h4 < GP; h4 += 4)
+                            *reinterpret_cast<float4*>(lg + h4) =
+                                make_float4(h4 + 0 < G ? s[u][h4 + 0 < G ? h4 + 0 : 0] : 0.f, h4 + 1 < G ? s[u][h4 + 1 < G ? h4 + 1 : 0] : 0.f,
+                                            h4 + 2 < G ? s[u][h4 + 2 < G ? h4 + 2 : 0] : 0.f, h4 + 3 < G ? s[u][h4 + 3 < G ? h4 + 3 : 0] : 0.f);
+                    }
+                }
             }
             float p[VU][G];
 #pragma unroll
@@ -646,8 +666,9 @@ __global__ __launch_bounds__((AttnCfg<T, D, G>::THREADS)) void attn_kernel(const
         // merged maximum M_h and the exact (unrounded) normaliser L_h.  Every live slot gains its weight
         // in the chunk plane and in the windows that reach back to this step; the slot appended at this
         // step starts all six planes afresh.
-        float* s_lx = reinterpret_cast<float*>(reinterpret_cast<unsigned char*>(s_corr + WAVES * GP + 4) + (size_t)WAVES * C::KT * C::KRS);
-        float* s_invL = s_lx + NG * G;
+        // exact normaliser partials: the bf16 D = 128 path keeps them apart from the rounded ones it uses for P.V
+        const float* s_lx = C::PVM ? smem + C::LX_OFFSET : s_l;
+        float* s_invL = smem + C::LX_OFFSET + NG * G;
         if (tid < G) {
             float ls = 0.f;
 #pragma unroll 8
@@ -711,7 +732,7 @@ __global__ __launch_bounds__((AttnCfg<T, D, G>::THREADS)) void attn_kernel(const
 template <typename T, int D, int G>
 static fk_status attn_launch(const fk_cache_desc* d, const AttnParams& base, int max_len, void* ws, hipStream_t st) {
     using C = AttnCfg<T, D, G>;
-    if constexpr (C::PVM) {
+    {
         if (base.feat) {  // feature variant: one workgroup per row, the logit scratch sits behind the counters
             AttnParams P = base;
             P.split_len = (d->capacity + 31) / 32 * 32;  // the whole row, whatever max_len says
@@ -730,7 +751,6 @@ static fk_status attn_launch(const fk_cache_desc* d, const AttnParams& base, int
             return launch_status();
         }
     }
-    if (base.feat) return FK_ERR_UNSUPPORTED;
     const AttnPlan p = attn_plan(d, max_len);
     const int rows = d->batch * d->n_kv_heads;
     AttnParams P = base;
@@ -854,7 +874,6 @@ extern "C" fk_status fk_decode_step_feat(const fk_cache_desc* desc, const void* 
         !aligned16(feat))
         return FK_ERR_INVALID_ARG;
     if (chunk_len <= 0 || chunk_pos < 0 || chunk_pos >= chunk_len) return FK_ERR_INVALID_ARG;
-    if (desc->dtype != FK_BF16 || desc->head_dim != 128) return FK_ERR_UNSUPPORTED;
     AttnParams P = {};
     P.q = q;
     P.K = K;

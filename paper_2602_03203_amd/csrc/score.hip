@@ -244,6 +244,7 @@ __global__ __launch_bounds__(kScoreThreads) void score_mfma_kernel(
 // accumulated in order.  T = float or bf16 storage.
 template <typename T, int D>
 __global__ __launch_bounds__(128) void score_simple_kernel(const T* __restrict__ K, const T* __restrict__ V,
+                                                           const float* __restrict__ feat, int g,
                                                            const int32_t* __restrict__ len,
                                                            const T* __restrict__ W1, const float* __restrict__ b1,
                                                            const float* __restrict__ W2, const float* __restrict__ b2,
@@ -256,7 +257,13 @@ __global__ __launch_bounds__(128) void score_simple_kernel(const T* __restrict__
     const int p = blockIdx.x * blockDim.x + threadIdx.x;
     if (p >= n) return;
     const int hw = per_head ? hkv : 0;
-    const T* w = W1 + (size_t)hw * 2 * D * H;
+    const int A = feat ? kFeatPlanes * g : 0;  // attention features behind k and v
+    const int GP = g <= 4 ? 4 : 8;
+    const T* w = W1 + (size_t)hw * (2 * D + A) * H;
+    auto wval = [](const T* ptr) -> float {
+        if constexpr (sizeof(T) == 4) return *ptr;
+        else return __uint_as_float(((uint32_t)*ptr) << 16);
+    };
     const T* krow = K + ((size_t)row * cap + p) * D;
     const T* vrow = V + ((size_t)row * cap + p) * D;
     float phi = 0.f;
@@ -284,6 +291,18 @@ __global__ __launch_bounds__(128) void score_simple_kernel(const T* __restrict__
                     }
                 }
             }
+        }
+        for (int a = 0; a < A; ++a) {  // feature a = head * 6 + plane; carried planes include this chunk
+            const int head = a / kFeatPlanes, pl = a % kFeatPlanes;
+            const float* fp = feat + (size_t)row * kFeatPlanes * cap * GP + (size_t)p * GP + head;
+            const size_t plane = (size_t)cap * GP;
+            float x = fp[pl * plane];
+            if (pl == 4) x += fp[3 * plane];
+            if (pl == 5) x = fmaf(kFeatDecay, x, fp[3 * plane]);
+            const T* wr = w + (size_t)(2 * D + a) * H + j0;
+#pragma unroll
+            for (int jj = 0; jj < 8; ++jj)
+                if (j0 + jj < H) z[jj] = fmaf(x, wval(wr + jj), z[jj]);
         }
 #pragma unroll
         for (int jj = 0; jj < 8; ++jj)
@@ -322,11 +341,11 @@ static fk_status score_mfma_launch(const fk_cache_desc* d, const void* K, const 
 }
 
 template <typename T, int D>
-static fk_status score_simple_launch(const fk_cache_desc* d, const void* K, const void* V, const int32_t* len,
-                                     int max_len, const fk_scorer* sc, float* scores, hipStream_t st) {
+static fk_status score_simple_launch(const fk_cache_desc* d, const void* K, const void* V, const float* feat,
+                                     const int32_t* len, int max_len, const fk_scorer* sc, float* scores, hipStream_t st) {
     const int rows = d->batch * d->n_kv_heads;
     hipLaunchKernelGGL((score_simple_kernel<T, D>), dim3((max_len + 127) / 128, rows), dim3(128), 0, st,
-                       (const T*)K, (const T*)V, len, (const T*)sc->w1, sc->b1, sc->w2, sc->b2, sc->hidden,
+                       (const T*)K, (const T*)V, feat, d->n_q_heads / d->n_kv_heads, len, (const T*)sc->w1, sc->b1, sc->w2, sc->b2, sc->hidden,
                        sc->per_head, d->n_kv_heads, d->capacity, scores);
     return launch_status();
 }
@@ -346,8 +365,8 @@ extern "C" fk_status fk_score_kv(const fk_cache_desc* desc, const void* K, const
     hipStream_t st = (hipStream_t)stream;
     const int D = desc->head_dim, H = scorer->hidden;
     if (desc->dtype == FK_F32) {
-        if (D == 64) return score_simple_launch<float, 64>(desc, K, V, len, max_len, scorer, scores, st);
-        return score_simple_launch<float, 128>(desc, K, V, len, max_len, scorer, scores, st);
+        if (D == 64) return score_simple_launch<float, 64>(desc, K, V, nullptr, len, max_len, scorer, scores, st);
+        return score_simple_launch<float, 128>(desc, K, V, nullptr, len, max_len, scorer, scores, st);
     }
     const bool mfma_ok = (H % 32 == 0) && score_lds_bytes(D, H) <= 160 * 1024;
     if (!mfma_ok) return FK_ERR_UNSUPPORTED;
@@ -364,19 +383,27 @@ extern "C" fk_status fk_score_kv_feat(const fk_cache_desc* desc, const void* K, 
     if (!scorer->w1 || !scorer->b1 || !scorer->w2 || !scorer->b2 || scorer->hidden <= 0) return FK_ERR_INVALID_ARG;
     if (max_len <= 0 || max_len > desc->capacity) return FK_ERR_INVALID_ARG;
     if (!aligned16(K) || !aligned16(V) || !aligned16(scorer->w1) || !aligned16(feat)) return FK_ERR_INVALID_ARG;
-    if (desc->dtype != FK_BF16 || desc->head_dim != 128) return FK_ERR_UNSUPPORTED;
-    const int g = desc->n_q_heads / desc->n_kv_heads, H = scorer->hidden;
-    if (H % 32 != 0 || score_lds_bytes(128, H, g) > 160 * 1024) return FK_ERR_UNSUPPORTED;
+    const int g = desc->n_q_heads / desc->n_kv_heads, H = scorer->hidden, D = desc->head_dim;
     hipStream_t st = (hipStream_t)stream;
-    switch (g) {
-        case 1: return score_mfma_launch<128, 1>(desc, K, V, feat, len, max_len, scorer, scores, st);
-        case 2: return score_mfma_launch<128, 2>(desc, K, V, feat, len, max_len, scorer, scores, st);
-        case 3: return score_mfma_launch<128, 3>(desc, K, V, feat, len, max_len, scorer, scores, st);
-        case 4: return score_mfma_launch<128, 4>(desc, K, V, feat, len, max_len, scorer, scores, st);
-        case 5: return score_mfma_launch<128, 5>(desc, K, V, feat, len, max_len, scorer, scores, st);
-        case 6: return score_mfma_launch<128, 6>(desc, K, V, feat, len, max_len, scorer, scores, st);
-        case 7: return score_mfma_launch<128, 7>(desc, K, V, feat, len, max_len, scorer, scores, st);
-        case 8: return score_mfma_launch<128, 8>(desc, K, V, feat, len, max_len, scorer, scores, st);
+    if (desc->dtype == FK_F32) {
+        if (D == 64) return score_simple_launch<float, 64>(desc, K, V, feat, len, max_len, scorer, scores, st);
+        return score_simple_launch<float, 128>(desc, K, V, feat, len, max_len, scorer, scores, st);
     }
+    if (H % 32 != 0 || score_lds_bytes(D, H, g) > 160 * 1024) return FK_ERR_UNSUPPORTED;
+#define FK_SCORE_FEAT_CASE(GG)                                                                              \
+    case GG:                                                                                                \
+        return D == 64 ? score_mfma_launch<64, GG>(desc, K, V, feat, len, max_len, scorer, scores, st)      \
+                       : score_mfma_launch<128, GG>(desc, K, V, feat, len, max_len, scorer, scores, st);
+    switch (g) {
+        FK_SCORE_FEAT_CASE(1)
+        FK_SCORE_FEAT_CASE(2)
+        FK_SCORE_FEAT_CASE(3)
+        FK_SCORE_FEAT_CASE(4)
+        FK_SCORE_FEAT_CASE(5)
+        FK_SCORE_FEAT_CASE(6)
+        FK_SCORE_FEAT_CASE(7)
+        FK_SCORE_FEAT_CASE(8)
+    }
+#undef FK_SCORE_FEAT_CASE
     return FK_ERR_UNSUPPORTED;
 }

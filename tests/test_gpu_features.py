@@ -165,17 +165,35 @@ def test_qwen3_4b_layer_shape_sampled_rows(gpu, ora):
     assert lockstep_feat(gpu, ora, w, 300, sample_rows=[(0, 0), (7, 3), (15, 7)], check_every=16) >= 2
 
 
-def test_unsupported_shapes_are_refused(gpu):
+@pytest.mark.parametrize("g,dtype,D", [(4, "f32", 64), (2, "bf16", 64), (3, "f32", 128), (7, "bf16", 64), (5, "f32", 64)])
+def test_other_storage_types_and_head_sizes(gpu, ora, g, dtype, D):
+    """fp32 (vector-ALU attention, one-thread-per-pair scorer) and head_dim 64 (MFMA q.K^T only)."""
+    w = small(g, dtype=dtype, head_dim=D)
+    assert lockstep_feat(gpu, ora, w, 200) == 3
+
+
+def test_tiny_workload_full_run_with_features(gpu, ora):
+    """configs[0] end to end (fp32, head_dim 64, 512 steps, 16 event clocks) with the feature path."""
+    w = si.config(0)
+    assert lockstep_feat(gpu, ora, w, w.steps) == 16
+
+
+def test_bad_arguments_are_refused(gpu):
     import paper_2602_03203_amd as fk
-    d = fk.CacheDesc(1, 4, 1, 64, 64, "bf16")
-    z = torch.zeros(64 * 64 * 4, dtype=torch.bfloat16, device="cuda")
+    z = torch.zeros(64 * 128 * 4, dtype=torch.bfloat16, device="cuda")
     f = torch.zeros(6 * 64 * 4, dtype=torch.float32, device="cuda")
     i = torch.zeros(64, dtype=torch.int32, device="cuda")
     ws = torch.zeros(1 << 16, dtype=torch.uint8, device="cuda")
-    with pytest.raises(fk.FkError) as e:
-        fk.fk_decode_step_feat(d, z, z, z, i, i, z, z, i, 8, 1.0, f, 0, 4, z, ws)
-    assert e.value.code == 2
     d = fk.CacheDesc(1, 4, 1, 128, 64, "bf16")
     with pytest.raises(fk.FkError) as e:
         fk.fk_decode_step_feat(d, z, z, z, i, i, z, z, i, 8, 1.0, f, 4, 4, z, ws)   # chunk_pos out of range
     assert e.value.code == 1
+    with pytest.raises(fk.FkError) as e:
+        fk.fk_decode_step_feat(d, z, z, z, i, i, z, z, i, 8, 1.0, f, 0, 4, z, ws[:64])   # workspace too small
+    assert e.value.code == 3
+    W1 = torch.zeros((1, 2 * 128 + 24, 48), dtype=torch.bfloat16, device="cuda")         # hidden not a multiple of 32
+    b = torch.zeros((1, 48), dtype=torch.float32, device="cuda")
+    sc = torch.zeros((1, 1, 64), dtype=torch.float32, device="cuda")
+    with pytest.raises(fk.FkError) as e:
+        fk.fk_score_kv_feat(d, z, z, f, i, 8, W1, b, b, b[:, 0].contiguous(), sc)
+    assert e.value.code == 2
