@@ -141,6 +141,12 @@ def test_small_runs_every_row_every_step(gpu, ora, g):
     assert lockstep_feat(gpu, ora, w, 300) == 4
 
 
+def test_events_on_rows_still_under_budget(gpu, ora):
+    """Short prompt: the first two events find every row under budget (the chunk is closed, nothing moves)."""
+    w = small(4, prompt=60)
+    assert lockstep_feat(gpu, ora, w, 260) == 4
+
+
 def test_interval_shorter_than_the_windows(gpu, ora):
     """L = 16: the 16- and 32-query windows cover the whole chunk, the 8-query window half of it."""
     w = small(4, interval=16, budget=96, prompt=90)
