@@ -22,6 +22,11 @@
 // MFMA result layout.  The vector ALUs only do the softmax.
 // bf16, D = 64.  q.K^T on MFMA with the K operand loaded directly, P.V as fp32 FMA.
 // fp32.  q.K^T as fp32 FMA plus a DPP row reduction, P.V as fp32 FMA.
+//
+// fk_decode_step_feat (FEAT variant, Appendix B.1).  One workgroup per row.  The scaled base-2 logits
+// are stored to a per-row scratch as they are formed; after the wavefront merge, with the final maximum
+// and normaliser known, a second pass turns them into attention weights and adds them to the open
+// planes of the row's feature state.
 #include "fk_common.h"
 
 namespace fk {

@@ -1,4 +1,4 @@
-// fk_append and fk_compact: the two calls that rewrite the cache.
+// fk_append, fk_compact and fk_compact_feat: the calls that rewrite the cache (and the attention-feature state).
 #include "fk_common.h"
 
 namespace fk {
