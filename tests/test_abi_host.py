@@ -74,3 +74,42 @@ def test_argument_validation_without_gpu(fklib):
     assert L.fk_score_kv(ctypes.byref(good), p, p, p, 512, ctypes.byref(S(p, p, p, p, 48, 1)), p, 0) == fklib.FK_ERR_UNSUPPORTED
     assert L.fk_score_kv(ctypes.byref(good), p, p, p, 512, ctypes.byref(S(0, p, p, p, 64, 1)), p, 0) == fklib.FK_ERR_INVALID_ARG
     assert L.fk_score_kv(ctypes.byref(good), p, p, p, 512, ctypes.byref(S(p, p, p, p, 4096, 1)), p, 0) == fklib.FK_ERR_UNSUPPORTED
+
+
+def test_argument_validation_of_the_next_row_calls(fklib):
+    """Sampled selection, the feature path and the Golden Eviction builder reject bad arguments on the host."""
+    L = fklib.lib()
+    D = fklib.fk_cache_desc
+    good = D(2, 8, 2, 128, 512, fklib.FK_BF16)
+    p = 4096
+    big = D(1, 8, 2, 128, 1 << 20, fklib.FK_BF16)
+    assert L.fk_select_keep_sampled(ctypes.byref(good), p, 0, p, p, 512, 256, 32, 64, p, 0) == fklib.FK_ERR_INVALID_ARG   # no noise
+    assert L.fk_select_keep_sampled(ctypes.byref(good), p, p, p, p, 512, 256, 32, -1, p, 0) == fklib.FK_ERR_INVALID_ARG
+    assert L.fk_select_keep_sampled(ctypes.byref(big), p, p, p, p, 1 << 20, 256, 32, 64, p, 0) == fklib.FK_ERR_UNSUPPORTED
+    # feature path
+    need = L.fk_decode_step_feat_workspace(ctypes.byref(good))
+    assert need >= 2 * 2 * 512 * 4 * 4
+    assert L.fk_decode_step_feat_workspace(ctypes.byref(D(2, 7, 2, 128, 512, 1))) == 0
+    args = [p] * 8
+    assert L.fk_decode_step_feat(ctypes.byref(good), *args, 512, 1.0, 0, 0, 128, p, p, need, 0) == fklib.FK_ERR_INVALID_ARG   # no state
+    assert L.fk_decode_step_feat(ctypes.byref(good), *args, 512, 1.0, p, 128, 128, p, p, need, 0) == fklib.FK_ERR_INVALID_ARG  # chunk_pos
+    assert L.fk_decode_step_feat(ctypes.byref(good), *args, 512, 1.0, p, 0, 0, p, p, need, 0) == fklib.FK_ERR_INVALID_ARG      # chunk_len
+    assert L.fk_decode_step_feat(ctypes.byref(good), *args, 512, 1.0, p, 0, 128, p, p, need - 1, 0) == fklib.FK_ERR_WORKSPACE
+    S = fklib.fk_scorer
+    assert L.fk_score_kv_feat(ctypes.byref(good), p, p, 0, p, 512, ctypes.byref(S(p, p, p, p, 64, 1)), p, 0) == fklib.FK_ERR_INVALID_ARG
+    assert L.fk_score_kv_feat(ctypes.byref(good), p, p, p, p, 512, ctypes.byref(S(p, p, p, p, 48, 1)), p, 0) == fklib.FK_ERR_UNSUPPORTED
+    assert L.fk_compact_feat(ctypes.byref(good), p, p, p, 0, p, p, 256, 0) == fklib.FK_ERR_INVALID_ARG
+    assert L.fk_compact_feat(ctypes.byref(good), p, p, p, p, p, p, 513, 0) == fklib.FK_ERR_INVALID_ARG
+    # Golden Eviction
+    assert L.fk_golden_steps(8192, 2048, 128) == 47 and L.fk_golden_steps(2176, 2048, 128) == 0
+    assert L.fk_golden_steps(0, 2048, 128) == -1 and L.fk_golden_steps(100, 8, 16) == -1
+    assert L.fk_golden_scores(0, 1, 8, 2, 512, 512, 64, 16, p, p, 0) == fklib.FK_ERR_INVALID_ARG
+    assert L.fk_golden_scores(p, 1, 8, 3, 512, 512, 64, 16, p, p, 0) == fklib.FK_ERR_INVALID_ARG       # heads do not divide
+    assert L.fk_golden_scores(p, 1, 8, 2, 512, 510, 64, 16, p, p, 0) == fklib.FK_ERR_INVALID_ARG       # ld < T
+    assert L.fk_golden_scores(p, 1, 8, 2, 510, 516, 64, 16, p, p, 0) == fklib.FK_ERR_INVALID_ARG       # ld not a multiple of 8
+    assert L.fk_golden_scores(p, 7, 8, 2, 512, 512, 64, 16, p, p, 0) == fklib.FK_ERR_UNSUPPORTED       # dtype
+    assert L.fk_golden_scores(p, 1, 8, 2, 512, 512, 16, 64, p, p, 0) == fklib.FK_ERR_INVALID_ARG       # L > B
+    assert L.fk_golden_scores(p, 1, 8, 2, 64, 64, 64, 16, p, p, 0) == fklib.FK_OK                       # M == 0: nothing to do
+    assert L.fk_golden_trace(0, 2, 512, 64, 16, p, 0) == fklib.FK_ERR_INVALID_ARG
+    assert L.fk_golden_trace(p, 2, 100000, 20000, 16, p, 0) == fklib.FK_ERR_UNSUPPORTED
+    assert L.fk_golden_trace(p, 2, 64, 64, 16, p, 0) == fklib.FK_OK
