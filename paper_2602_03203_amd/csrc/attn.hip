@@ -746,12 +746,8 @@ static fk_status attn_launch(const fk_cache_desc* d, const AttnParams& base, int
             P.rec = nullptr;
             P.logit = reinterpret_cast<float*>(reinterpret_cast<char*>(ws) + attn_counter_bytes(d));
             auto kern = attn_kernel<T, D, G, true>;
-            static bool attr_set = false;
-            if (!attr_set) {
-                if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)C::LDS_BYTES_FEAT) != hipSuccess)
-                    return FK_ERR_LAUNCH;
-                attr_set = true;
-            }
+            static bool lds_ok[kMaxDevices] = {};  // per template instantiation
+            if (!allow_dynamic_lds((const void*)kern, C::LDS_BYTES_FEAT, lds_ok)) return FK_ERR_LAUNCH;
             hipLaunchKernelGGL(kern, dim3(1, d->batch * d->n_kv_heads), dim3(C::THREADS), C::LDS_BYTES_FEAT, st, P);
             return launch_status();
         }
@@ -764,12 +760,8 @@ static fk_status attn_launch(const fk_cache_desc* d, const AttnParams& base, int
     P.row_cnt = reinterpret_cast<uint32_t*>(ws);
     P.rec = reinterpret_cast<float*>(reinterpret_cast<char*>(ws) + attn_counter_bytes(d));
     auto kern = attn_kernel<T, D, G, false>;
-    static bool attr_set = false;  // per template instantiation
-    if (!attr_set) {
-        if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)C::LDS_BYTES) != hipSuccess)
-            return FK_ERR_LAUNCH;
-        attr_set = true;
-    }
+    static bool lds_ok[kMaxDevices] = {};  // per template instantiation
+    if (!allow_dynamic_lds((const void*)kern, C::LDS_BYTES, lds_ok)) return FK_ERR_LAUNCH;
     hipLaunchKernelGGL(kern, dim3(p.nsplit, rows), dim3(C::THREADS), C::LDS_BYTES, st, P);
     return launch_status();
 }

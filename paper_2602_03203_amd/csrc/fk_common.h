@@ -84,6 +84,19 @@ inline fk_status check_desc(const fk_cache_desc* d) {
 
 inline fk_status launch_status() { return hipGetLastError() == hipSuccess ? FK_OK : FK_ERR_LAUNCH; }
 
+// Raise a kernel's dynamic-LDS limit once per device (the attribute belongs to the function on the current
+// device).  `done` is the caller's static flag array, one per kernel.  Concurrent first calls both set it: harmless.
+static constexpr int kMaxDevices = 64;
+inline bool allow_dynamic_lds(const void* kernel, size_t bytes, bool (&done)[kMaxDevices]) {
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return false;
+    if (!done[dev]) {
+        if (hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes) != hipSuccess) return false;
+        done[dev] = true;
+    }
+    return true;
+}
+
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
 }  // namespace fk

@@ -198,13 +198,8 @@ extern "C" fk_status fk_golden_trace(const float* alpha, int32_t n_kv_heads, int
     const int M = golden_steps(T, budget, interval);
     if (M == 0) return FK_OK;
     const size_t lds = sizeof(int32_t) * ((size_t)budget + interval) + sizeof(uint32_t) * (size_t)budget;
-    static bool attr_set = false;
-    if (!attr_set) {
-        if (hipFuncSetAttribute((const void*)golden_trace_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                (int)(sizeof(int32_t) * 2 * kTraceMaxCache)) != hipSuccess)
-            return FK_ERR_LAUNCH;
-        attr_set = true;
-    }
+    static bool lds_ok[kMaxDevices] = {};
+    if (!allow_dynamic_lds((const void*)golden_trace_kernel, sizeof(int32_t) * 2 * kTraceMaxCache, lds_ok)) return FK_ERR_LAUNCH;
     hipLaunchKernelGGL(golden_trace_kernel, dim3(n_kv_heads), dim3(kSelThreads), lds, (hipStream_t)stream, alpha, T, M,
                        budget, interval, kept);
     return launch_status();

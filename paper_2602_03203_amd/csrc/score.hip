@@ -332,8 +332,8 @@ static fk_status score_mfma_launch(const fk_cache_desc* d, const void* K, const 
     ppb = (ppb + tile - 1) / tile * tile;
     chunks = (max_len + ppb - 1) / ppb;
     auto kern = score_mfma_kernel<D, NT, GF>;
-    if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
-        return FK_ERR_LAUNCH;
+    static bool lds_ok[kMaxDevices] = {};  // per template instantiation; the limit covers every hidden width it admits
+    if (!allow_dynamic_lds((const void*)kern, 160 * 1024, lds_ok)) return FK_ERR_LAUNCH;
     hipLaunchKernelGGL(kern, dim3(chunks, rows), dim3(kScoreThreads), lds, st, (const bf16_t*)K,
                        (const bf16_t*)V, feat, len, (const bf16_t*)sc->w1, sc->b1, sc->w2, sc->b2, sc->hidden,
                        sc->per_head, d->n_kv_heads, d->capacity, ppb, scores);
