@@ -394,6 +394,19 @@ def main():
                    "scorer_inputs": "k, v, attention features" if args.features else "k, v"},
         "path_gbs_algorithmic": total_attn_bytes / wall / 1e9,
     }
+    # the same with the eviction events' algorithmic bytes added (rows over budget at the event: every retained
+    # pair scored, its score read by the selection, the kept slots written, every kept pair that is not already in
+    # place moved; "every kept pair" is taken, an upper bound)
+    ev_bytes = 0.0
+    for t in range(L - 1, K_steps, L):
+        over = lens_at[t] > B
+        pairs = float(lens_at[t][over].sum()) * w.n_kv_heads
+        rows_over = float(over.sum()) * w.n_kv_heads
+        ev_bytes += pairs * (2 * w.head_dim * w.elem_bytes + 4) + 4 * pairs + rows_over * 4 * B \
+            + rows_over * B * (4 * w.head_dim * w.elem_bytes + 8)
+    result["path_with_events"] = {"gbs_algorithmic": (total_attn_bytes + ev_bytes) / wall / 1e9,
+                                  "frac_of_hbm_peak": (total_attn_bytes + ev_bytes) / wall / 1e9 / HBM_PEAK_GBS,
+                                  "event_bytes_share": ev_bytes / (total_attn_bytes + ev_bytes)}
 
     if not args.no_kernel_timing:
         # second pass over the same steps with HIP events (on the launch stream) bracketing the attention
