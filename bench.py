@@ -344,9 +344,9 @@ def main():
                     ev_kernels.append((t, kev))
                     kev[0].record(stream)
                 if feat is None:
-                    fk.fk_score_kv(desc, Kc, Vc, lenc, ml, *dW, scores, stream)
+                    fk.fk_score_kv(desc, Kc, Vc, lenc, ml, *dW, scores, stream, skip_len=B)
                 else:
-                    fk.fk_score_kv_feat(desc, Kc, Vc, feat, lenc, ml, *dW, scores, stream)
+                    fk.fk_score_kv_feat(desc, Kc, Vc, feat, lenc, ml, *dW, scores, stream, skip_len=B)
                 if kev:
                     kev[1].record(stream)
                 if noise_pool is None:

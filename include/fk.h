@@ -69,6 +69,8 @@ typedef struct {
     const float *b2;  /* device [n_sets] */
     int32_t hidden;   /* H; bf16: multiple of 32 with H*(2*head_dim+8)*2 + 8*H <= 160 KiB of LDS */
     int32_t per_head; /* 1: n_sets = n_kv_heads, one model per KV head; 0: one shared model */
+    int32_t skip_len; /* rows with len[r] <= skip_len are skipped, their scores not written (pass the budget:
+                         rows at or under budget are not pruned and need no scores); 0 scores every row */
 } fk_scorer;
 
 const char *fk_status_string(fk_status s);

@@ -32,7 +32,7 @@ class fk_cache_desc(ctypes.Structure):
 
 class fk_scorer(ctypes.Structure):
     _fields_ = [("w1", ctypes.c_void_p), ("b1", ctypes.c_void_p), ("w2", ctypes.c_void_p), ("b2", ctypes.c_void_p),
-                ("hidden", ctypes.c_int32), ("per_head", ctypes.c_int32)]
+                ("hidden", ctypes.c_int32), ("per_head", ctypes.c_int32), ("skip_len", ctypes.c_int32)]
 
 
 class FkError(RuntimeError):
@@ -149,10 +149,12 @@ def fk_decode_step(desc: CacheDesc, q, K, V, pos, length, k_new, v_new, pos_new,
                                 _ptr(workspace), nbytes, _stream(stream)), "fk_decode_step")
 
 
-def fk_score_kv(desc: CacheDesc, K, V, length, max_len: int, W1, b1, W2, b2, scores, stream=None) -> None:
-    """W1 [n_sets, 2D, H] cache dtype; b1, W2 [n_sets, H] fp32; b2 [n_sets] fp32; n_sets in {1, n_kv_heads}."""
+def fk_score_kv(desc: CacheDesc, K, V, length, max_len: int, W1, b1, W2, b2, scores, stream=None, skip_len: int = 0) -> None:
+    """W1 [n_sets, 2D, H] cache dtype; b1, W2 [n_sets, H] fp32; b2 [n_sets] fp32; n_sets in {1, n_kv_heads};
+    rows with len <= skip_len are not scored."""
     n_sets, _, hidden = W1.shape
-    sc = fk_scorer(_ptr(W1), _ptr(b1), _ptr(W2), _ptr(b2), int(hidden), 1 if n_sets == desc.n_kv_heads and n_sets > 1 else 0)
+    sc = fk_scorer(_ptr(W1), _ptr(b1), _ptr(W2), _ptr(b2), int(hidden), 1 if n_sets == desc.n_kv_heads and n_sets > 1 else 0,
+                   int(skip_len))
     _check(lib().fk_score_kv(ctypes.byref(desc.c()), _ptr(K), _ptr(V), _ptr(length), int(max_len), ctypes.byref(sc),
                              _ptr(scores), _stream(stream)), "fk_score_kv")
 
@@ -199,10 +201,12 @@ def fk_decode_step_feat(desc: CacheDesc, q, K, V, pos, length, k_new, v_new, pos
                                      _stream(stream)), "fk_decode_step_feat")
 
 
-def fk_score_kv_feat(desc: CacheDesc, K, V, feat, length, max_len: int, W1, b1, W2, b2, scores, stream=None) -> None:
+def fk_score_kv_feat(desc: CacheDesc, K, V, feat, length, max_len: int, W1, b1, W2, b2, scores, stream=None,
+                     skip_len: int = 0) -> None:
     """fk_score_kv on concat(k, v, a); W1 [n_sets, 2D + 6g, H]."""
     n_sets, _, hidden = W1.shape
-    sc = fk_scorer(_ptr(W1), _ptr(b1), _ptr(W2), _ptr(b2), int(hidden), 1 if n_sets == desc.n_kv_heads and n_sets > 1 else 0)
+    sc = fk_scorer(_ptr(W1), _ptr(b1), _ptr(W2), _ptr(b2), int(hidden), 1 if n_sets == desc.n_kv_heads and n_sets > 1 else 0,
+                   int(skip_len))
     _check(lib().fk_score_kv_feat(ctypes.byref(desc.c()), _ptr(K), _ptr(V), _ptr(feat), _ptr(length), int(max_len),
                                   ctypes.byref(sc), _ptr(scores), _stream(stream)), "fk_score_kv_feat")
 

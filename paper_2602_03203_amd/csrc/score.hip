@@ -71,7 +71,7 @@ __global__ __launch_bounds__(kScoreThreads) void score_mfma_kernel(
     const bf16_t* __restrict__ K, const bf16_t* __restrict__ V, const float* __restrict__ feat,
     const int32_t* __restrict__ len,
     const bf16_t* __restrict__ W1, const float* __restrict__ b1, const float* __restrict__ W2,
-    const float* __restrict__ b2, int H, int per_head, int n_kv, int cap, int pairs_per_block,
+    const float* __restrict__ b2, int H, int per_head, int skip_len, int n_kv, int cap, int pairs_per_block,
     float* __restrict__ scores) {
     using SC = ScoreCfg<D, GF>;
     constexpr int F = SC::F;
@@ -82,7 +82,7 @@ __global__ __launch_bounds__(kScoreThreads) void score_mfma_kernel(
     const int hkv = row % n_kv;
     const int n = min(len[row], cap);
     const int p_begin = blockIdx.x * pairs_per_block;
-    if (p_begin >= n) return;
+    if (p_begin >= n || n <= skip_len) return;
     const int p_end = min(p_begin + pairs_per_block, n);
     const int hw = per_head ? hkv : 0;
 
@@ -248,14 +248,14 @@ __global__ __launch_bounds__(128) void score_simple_kernel(const T* __restrict__
                                                            const int32_t* __restrict__ len,
                                                            const T* __restrict__ W1, const float* __restrict__ b1,
                                                            const float* __restrict__ W2, const float* __restrict__ b2,
-                                                           int H, int per_head, int n_kv, int cap,
+                                                           int H, int per_head, int skip_len, int n_kv, int cap,
                                                            float* __restrict__ scores) {
     constexpr int EPL = Vec16<T>::N;
     const int row = blockIdx.y;
     const int hkv = row % n_kv;
     const int n = min(len[row], cap);
     const int p = blockIdx.x * blockDim.x + threadIdx.x;
-    if (p >= n) return;
+    if (p >= n || n <= skip_len) return;
     const int hw = per_head ? hkv : 0;
     const int A = feat ? kFeatPlanes * g : 0;  // attention features behind k and v
     const int GP = g <= 4 ? 4 : 8;
@@ -336,7 +336,7 @@ static fk_status score_mfma_launch(const fk_cache_desc* d, const void* K, const 
     if (!allow_dynamic_lds((const void*)kern, 160 * 1024, lds_ok)) return FK_ERR_LAUNCH;
     hipLaunchKernelGGL(kern, dim3(chunks, rows), dim3(kScoreThreads), lds, st, (const bf16_t*)K,
                        (const bf16_t*)V, feat, len, (const bf16_t*)sc->w1, sc->b1, sc->w2, sc->b2, sc->hidden,
-                       sc->per_head, d->n_kv_heads, d->capacity, ppb, scores);
+                       sc->per_head, sc->skip_len, d->n_kv_heads, d->capacity, ppb, scores);
     return launch_status();
 }
 
@@ -346,7 +346,7 @@ static fk_status score_simple_launch(const fk_cache_desc* d, const void* K, cons
     const int rows = d->batch * d->n_kv_heads;
     hipLaunchKernelGGL((score_simple_kernel<T, D>), dim3((max_len + 127) / 128, rows), dim3(128), 0, st,
                        (const T*)K, (const T*)V, feat, d->n_q_heads / d->n_kv_heads, len, (const T*)sc->w1, sc->b1, sc->w2, sc->b2, sc->hidden,
-                       sc->per_head, d->n_kv_heads, d->capacity, scores);
+                       sc->per_head, sc->skip_len, d->n_kv_heads, d->capacity, scores);
     return launch_status();
 }
 
@@ -359,7 +359,7 @@ extern "C" fk_status fk_score_kv(const fk_cache_desc* desc, const void* K, const
     fk_status s = check_desc(desc);
     if (s != FK_OK) return s;
     if (!K || !V || !len || !scorer || !scores) return FK_ERR_INVALID_ARG;
-    if (!scorer->w1 || !scorer->b1 || !scorer->w2 || !scorer->b2 || scorer->hidden <= 0) return FK_ERR_INVALID_ARG;
+    if (!scorer->w1 || !scorer->b1 || !scorer->w2 || !scorer->b2 || scorer->hidden <= 0 || scorer->skip_len < 0) return FK_ERR_INVALID_ARG;
     if (max_len <= 0 || max_len > desc->capacity) return FK_ERR_INVALID_ARG;
     if (!aligned16(K) || !aligned16(V) || !aligned16(scorer->w1)) return FK_ERR_INVALID_ARG;
     hipStream_t st = (hipStream_t)stream;
@@ -380,7 +380,7 @@ extern "C" fk_status fk_score_kv_feat(const fk_cache_desc* desc, const void* K, 
     fk_status s = check_desc(desc);
     if (s != FK_OK) return s;
     if (!K || !V || !feat || !len || !scorer || !scores) return FK_ERR_INVALID_ARG;
-    if (!scorer->w1 || !scorer->b1 || !scorer->w2 || !scorer->b2 || scorer->hidden <= 0) return FK_ERR_INVALID_ARG;
+    if (!scorer->w1 || !scorer->b1 || !scorer->w2 || !scorer->b2 || scorer->hidden <= 0 || scorer->skip_len < 0) return FK_ERR_INVALID_ARG;
     if (max_len <= 0 || max_len > desc->capacity) return FK_ERR_INVALID_ARG;
     if (!aligned16(K) || !aligned16(V) || !aligned16(scorer->w1) || !aligned16(feat)) return FK_ERR_INVALID_ARG;
     const int g = desc->n_q_heads / desc->n_kv_heads, H = scorer->hidden, D = desc->head_dim;

@@ -139,6 +139,17 @@ def test_score_kv_matches_oracle(gpu, ora, dtype, D, H, Hkv, cap, lens, per_head
     gpu.assert_scores_close(got, ref, lens, "scores")
     for b in range(Bt):                                   # slots past len are not written
         assert np.isnan(got[b, :, lens[b]:]).all()
+    # rows at or under skip_len (the budget, in the protocol) are left alone, the others get the same scores
+    skip = sorted(lens)[len(lens) // 2]
+    dev.scores.fill_(float("nan"))
+    fk.fk_score_kv(dev.desc, dev.K, dev.V, dev.len, cap, gpu.to_dev(W1), gpu.to_dev(b1), gpu.to_dev(W2), gpu.to_dev(b2), dev.scores,
+                   skip_len=skip)
+    got2 = dev.scores.cpu().numpy()
+    for b in range(Bt):
+        if lens[b] <= skip:
+            assert np.isnan(got2[b]).all()
+        else:
+            assert np.array_equal(got2[b, :, :lens[b]], got[b, :, :lens[b]])
 
 
 SELECT_CASES = [
