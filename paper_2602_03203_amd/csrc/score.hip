@@ -240,76 +240,82 @@ __global__ __launch_bounds__(kScoreThreads) void score_mfma_kernel(
     }
 }
 
-// fp32 (and fallback) path: one thread per pair, hidden units in chunks of 8, features
-// accumulated in order.  T = float or bf16 storage.
+// fp32 path.  A wavefront scores four pairs: their inputs x (k, v and, with features, a) are staged in LDS as
+// fp32; lane j owns the hidden units j, j + 64, ...; for every input feature the lane's W1 element (coalesced
+// over the lanes, shared by the four pairs) meets the four x values (LDS broadcasts).  Features are
+// accumulated in order, the hidden units are reduced over the wavefront in a fixed order.
+static constexpr int kSimpleWaves = 4;  // wavefronts per workgroup
+static constexpr int kSimplePairs = 4;  // pairs per wavefront
+
 template <typename T, int D>
-__global__ __launch_bounds__(128) void score_simple_kernel(const T* __restrict__ K, const T* __restrict__ V,
-                                                           const float* __restrict__ feat, int g,
-                                                           const int32_t* __restrict__ len,
-                                                           const T* __restrict__ W1, const float* __restrict__ b1,
-                                                           const float* __restrict__ W2, const float* __restrict__ b2,
-                                                           int H, int per_head, int skip_len, int n_kv, int cap,
-                                                           float* __restrict__ scores) {
-    constexpr int EPL = Vec16<T>::N;
+__global__ __launch_bounds__(kSimpleWaves * kWave) void score_simple_kernel(
+    const T* __restrict__ K, const T* __restrict__ V, const float* __restrict__ feat, int g,
+    const int32_t* __restrict__ len, const T* __restrict__ W1, const float* __restrict__ b1,
+    const float* __restrict__ W2, const float* __restrict__ b2, int H, int per_head, int skip_len, int n_kv, int cap,
+    float* __restrict__ scores) {
+    constexpr int PP = kSimplePairs;
+    extern __shared__ __attribute__((aligned(16))) float s_x[];  // [waves][PP][F]
     const int row = blockIdx.y;
     const int hkv = row % n_kv;
     const int n = min(len[row], cap);
-    const int p = blockIdx.x * blockDim.x + threadIdx.x;
-    if (p >= n || n <= skip_len) return;
+    if (n <= skip_len) return;
+    const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
+    const int p0 = (blockIdx.x * kSimpleWaves + wave) * PP;
     const int hw = per_head ? hkv : 0;
     const int A = feat ? kFeatPlanes * g : 0;  // attention features behind k and v
+    const int F = 2 * D + A;
     const int GP = g <= 4 ? 4 : 8;
-    const T* w = W1 + (size_t)hw * (2 * D + A) * H;
-    auto wval = [](const T* ptr) -> float {
+    const T* w = W1 + (size_t)hw * F * H;
+    auto widen = [](const T* ptr) -> float {
         if constexpr (sizeof(T) == 4) return *ptr;
         else return __uint_as_float(((uint32_t)*ptr) << 16);
     };
-    const T* krow = K + ((size_t)row * cap + p) * D;
-    const T* vrow = V + ((size_t)row * cap + p) * D;
-    float phi = 0.f;
-    for (int j0 = 0; j0 < H; j0 += 8) {
-        float z[8];
-#pragma unroll
-        for (int e = 0; e < 8; ++e) z[e] = 0.f;
-        for (int half = 0; half < 2; ++half) {
-            const T* xr = half == 0 ? krow : vrow;
-            for (int c = 0; c < D / EPL; ++c) {
-                float xf[EPL];
-                Vec16<T>::unpack(*reinterpret_cast<const uint4*>(xr + c * EPL), xf);
-#pragma unroll
-                for (int e = 0; e < EPL; ++e) {
-                    const int f = half * D + c * EPL + e;
-                    const T* wr = w + (size_t)f * H + j0;
-#pragma unroll
-                    for (int jj = 0; jj < 8; ++jj) {
-                        if (j0 + jj < H) {
-                            float wv;
-                            if constexpr (sizeof(T) == 4) wv = wr[jj];
-                            else wv = __uint_as_float(((uint32_t)wr[jj]) << 16);
-                            z[jj] = fmaf(xf[e], wv, z[jj]);
-                        }
-                    }
-                }
+    float* x = s_x + (size_t)wave * PP * F;
+    if (p0 < n) {
+        for (int p = 0; p < PP; ++p) {
+            const int pair = min(p0 + p, n - 1);
+            const T* krow = K + ((size_t)row * cap + pair) * D;
+            const T* vrow = V + ((size_t)row * cap + pair) * D;
+            for (int f = lane; f < 2 * D; f += kWave) x[p * F + f] = f < D ? widen(krow + f) : widen(vrow + f - D);
+            for (int a = lane; a < A; a += kWave) {  // feature a = head * 6 + plane; carried planes include this chunk
+                const int head = a / kFeatPlanes, pl = a % kFeatPlanes;
+                const float* fp = feat + (size_t)row * kFeatPlanes * cap * GP + (size_t)pair * GP + head;
+                const size_t plane = (size_t)cap * GP;
+                float v = fp[pl * plane];
+                if (pl == 4) v += fp[3 * plane];
+                if (pl == 5) v = fmaf(kFeatDecay, v, fp[3 * plane]);
+                x[p * F + 2 * D + a] = v;
             }
         }
-        for (int a = 0; a < A; ++a) {  // feature a = head * 6 + plane; carried planes include this chunk
-            const int head = a / kFeatPlanes, pl = a % kFeatPlanes;
-            const float* fp = feat + (size_t)row * kFeatPlanes * cap * GP + (size_t)p * GP + head;
-            const size_t plane = (size_t)cap * GP;
-            float x = fp[pl * plane];
-            if (pl == 4) x += fp[3 * plane];
-            if (pl == 5) x = fmaf(kFeatDecay, x, fp[3 * plane]);
-            const T* wr = w + (size_t)(2 * D + a) * H + j0;
-#pragma unroll
-            for (int jj = 0; jj < 8; ++jj)
-                if (j0 + jj < H) z[jj] = fmaf(x, wval(wr + jj), z[jj]);
-        }
-#pragma unroll
-        for (int jj = 0; jj < 8; ++jj)
-            if (j0 + jj < H)
-                phi = fmaf(gelu_erf_precise(z[jj] + b1[(size_t)hw * H + j0 + jj]), W2[(size_t)hw * H + j0 + jj], phi);
     }
-    scores[(size_t)row * cap + p] = phi + b2[hw];
+    __syncthreads();
+    if (p0 >= n) return;
+    float phi[PP];
+#pragma unroll
+    for (int p = 0; p < PP; ++p) phi[p] = 0.f;
+    for (int j = lane; j < (H + kWave - 1) / kWave * kWave; j += kWave) {
+        const bool live = j < H;
+        const T* wj = w + (live ? j : 0);
+        float z[PP];
+#pragma unroll
+        for (int p = 0; p < PP; ++p) z[p] = 0.f;
+        for (int f = 0; f < F; ++f) {
+            const float wv = widen(wj + (size_t)f * H);
+#pragma unroll
+            for (int p = 0; p < PP; ++p) z[p] = fmaf(x[p * F + f], wv, z[p]);
+        }
+        if (live) {
+            const float bb = b1[(size_t)hw * H + j], ww = W2[(size_t)hw * H + j];
+#pragma unroll
+            for (int p = 0; p < PP; ++p) phi[p] = fmaf(gelu_erf_precise(z[p] + bb), ww, phi[p]);
+        }
+    }
+    const float bias2 = b2[hw];
+#pragma unroll
+    for (int p = 0; p < PP; ++p) {
+        const float tot = group_sum<64>(phi[p]);
+        if (lane == 0 && p0 + p < n) scores[(size_t)row * cap + p0 + p] = tot + bias2;
+    }
 }
 
 // LDS of the MFMA kernel for group size gf of the feature part (0: no features)
@@ -344,7 +350,10 @@ template <typename T, int D>
 static fk_status score_simple_launch(const fk_cache_desc* d, const void* K, const void* V, const float* feat,
                                      const int32_t* len, int max_len, const fk_scorer* sc, float* scores, hipStream_t st) {
     const int rows = d->batch * d->n_kv_heads;
-    hipLaunchKernelGGL((score_simple_kernel<T, D>), dim3((max_len + 127) / 128, rows), dim3(128), 0, st,
+    const int g = d->n_q_heads / d->n_kv_heads;
+    const int per_block = kSimpleWaves * kSimplePairs;
+    const size_t lds = sizeof(float) * per_block * (2 * D + (feat ? kFeatPlanes * g : 0));
+    hipLaunchKernelGGL((score_simple_kernel<T, D>), dim3((max_len + per_block - 1) / per_block, rows), dim3(kSimpleWaves * kWave), lds, st,
                        (const T*)K, (const T*)V, feat, d->n_q_heads / d->n_kv_heads, len, (const T*)sc->w1, sc->b1, sc->w2, sc->b2, sc->hidden,
                        sc->per_head, sc->skip_len, d->n_kv_heads, d->capacity, scores);
     return launch_status();
