@@ -11,7 +11,7 @@ import pytest
 import torch
 
 import synth_inputs as si
-from util import bulk_step_inputs, scorer_storage, workload_cache
+from util import bulk_step_inputs, scorer_storage, workload_cache, workload_cache_replicated
 
 pytestmark = pytest.mark.gpu
 
@@ -26,7 +26,7 @@ def gpu():
     return gpu_util
 
 
-def lockstep(gpu, ora, w, n_steps, sample_rows=None, scale=None, check_every=1, fused=True, sampled=False):
+def lockstep(gpu, ora, w, n_steps, sample_rows=None, scale=None, check_every=1, fused=True, sampled=False, replicate=False):
     """Run the device on the whole workload and the oracle on `sample_rows` [(b, h), ...]
     (None = every row).  Returns the number of events checked."""
     import paper_2602_03203_amd as fk
@@ -34,7 +34,7 @@ def lockstep(gpu, ora, w, n_steps, sample_rows=None, scale=None, check_every=1, 
     lens0 = si.initial_lengths(w)
     B, L, g = w.budget, w.interval, w.group
     print(f"lockstep {w.name}: building prompt cache", flush=True)
-    full = workload_cache(ora, w)
+    full = workload_cache_replicated(ora, w, sample_rows) if replicate else workload_cache(ora, w)
     dev = gpu.DevCache(full, w.n_q_heads)
     W1, b1, W2, b2 = scorer_storage(w)
     dW = [gpu.to_dev(x) for x in (W1, b1, W2, b2)]
@@ -162,6 +162,28 @@ def test_ragged_batch_shape_sampled_rows(gpu, ora):
     b_short = int(np.argmin(lens0))
     rows = [(b_long, 0), (b_short, 5)]
     assert lockstep(gpu, ora, w, 260, sample_rows=rows, scale=128.0 ** 0.5, check_every=32) >= 2
+
+
+def test_stack_layer_shapes_at_full_batch_sampled_rows(gpu, ora):
+    """One layer of configs[2] (batch 8, B 16384: 64 rows, two splits per row) and of configs[3] (batch 16,
+    GQA 7, B 4096: 64 rows) in the launch configuration bench.py uses, caches just under the first event;
+    the oracle follows two rows of each, the other rows hold copies of their data."""
+    w = si.config(2).scaled(layers=1, prompt=16384 - 64)
+    assert lockstep(gpu, ora, w, 200, sample_rows=[(0, 0), (7, 5)], check_every=40, replicate=True) >= 1
+    w = si.config(3).scaled(layers=1, prompt=4096 - 32)
+    assert lockstep(gpu, ora, w, 140, sample_rows=[(2, 1), (15, 3)], check_every=20, replicate=True) >= 2
+
+
+def test_ragged_batch_at_full_size_sampled_rows(gpu, ora):
+    """configs[4] as bench.py runs it: 64 sequences (512 rows, 8.6 GB of cache), lengths 1024 .. 32768, B 8192;
+    the oracle follows one row far over budget, one under it and the longest one."""
+    w = si.config(4)
+    lens = si.initial_lengths(w)
+    over = int(np.argmax(lens > 20000))
+    under = int(np.argmax(lens < 8000))
+    longest = int(np.argmax(lens))
+    rows = sorted({(over, 0), (under, 3), (longest, 7)})
+    assert lockstep(gpu, ora, w, 130, sample_rows=rows, check_every=32, replicate=True) == 1
 
 
 def test_one_shot_prefill_compression(gpu, ora):

@@ -112,3 +112,37 @@ def bulk_step_inputs(w: si.Workload, layer, t0, t1, lens0, batch_sel=None, kv_he
         k[:, i] = si.storage_array(kk[0].transpose(1, 0, 2), w.dtype)
         v[:, i] = si.storage_array(vv[0].transpose(1, 0, 2), w.dtype)
     return q, k, v, pos
+
+
+def workload_cache_replicated(oracle, w: si.Workload, rows, layer=0):
+    """Prompt-filled cache of the whole workload in which only the (b, h) rows listed in ``rows`` hold the
+    generator's data; every other row is a copy of one of them, cut to its own sequence's length.  For full-size
+    parity runs: the device works on every row, the oracle follows ``rows`` only, and drawing tens of
+    gigabytes from the counter generator on the host would take minutes."""
+    lens = si.initial_lengths(w)
+    c = oracle.new_cache(w.dtype, w.batch, w.n_kv_heads, w.capacity, w.head_dim)
+    c.len[...] = lens
+    src = []
+    for (b, h) in rows:
+        n = int(lens[b])
+        K, V = si.gen_kv(w, layer, 0, n, batch_sel=[b], head_sel=[h])
+        c.K[b, h, :n] = si.storage_array(K, w.dtype)[0, 0]
+        c.V[b, h, :n] = si.storage_array(V, w.dtype)[0, 0]
+        src.append((b, h, n))
+    longest = max(src, key=lambda t: t[2])
+    i = 0
+    for b in range(w.batch):
+        n = int(lens[b])
+        c.pos[b, :, :n] = np.arange(n, dtype=np.int32)
+        for h in range(w.n_kv_heads):
+            if (b, h) in rows:
+                continue
+            sb, sh, sn = src[i % len(src)] if src[i % len(src)][2] >= n else longest
+            i += 1
+            m = min(n, sn)
+            c.K[b, h, :m], c.V[b, h, :m] = c.K[sb, sh, :m], c.V[sb, sh, :m]
+            if m < n:   # longer than any sampled row: repeat the source
+                for o in range(m, n, sn):
+                    e = min(o + sn, n)
+                    c.K[b, h, o:e], c.V[b, h, o:e] = c.K[sb, sh, :e - o], c.V[sb, sh, :e - o]
+    return c
