@@ -55,6 +55,21 @@ __device__ __forceinline__ void wait_stores_done() {
     __builtin_amdgcn_s_waitcnt(0x0F70);
 }
 
+// 16-byte load of streamed cache data.  NT marks it non-temporal: a cache that is larger than the Infinity Cache
+// (256 MB) is re-read from HBM every step anyway, and lines that are not kept in the caches make room faster
+// (+8 .. 11 % bandwidth measured at 0.5 .. 4 GB); below that size the plain load is the faster one.
+template <bool NT>
+__device__ __forceinline__ uint4 ld_stream(const uint4* p) {
+    if constexpr (NT) {
+        typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+        const u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p));
+        return make_uint4(v.x, v.y, v.z, v.w);
+    } else {
+        return *p;
+    }
+}
+static constexpr size_t kStreamNtBytes = (size_t)352 << 20;  // K + V bytes of a launch from which NT loads are used
+
 // i-th dword of a 16-byte register quad; i is a compile-time constant after unrolling
 __device__ __forceinline__ uint32_t dword_of(const uint4& v, int i) { return i == 0 ? v.x : (i == 1 ? v.y : (i == 2 ? v.z : v.w)); }
 
@@ -162,7 +177,7 @@ __device__ __forceinline__ float4 keep_if(bool c, const float4 p) {
     return make_float4(c ? p.x : 0.f, c ? p.y : 0.f, c ? p.z : 0.f, c ? p.w : 0.f);
 }
 
-template <typename T, int D, int G, bool FEAT>
+template <typename T, int D, int G, bool FEAT, bool NT>
 __global__ __launch_bounds__((AttnCfg<T, D, G>::THREADS)) void attn_kernel(const AttnParams P) {
     using C = AttnCfg<T, D, G>;
     constexpr int CH = C::CH, KG = C::KG, WAVES = C::WAVES, KT = C::KT, VU = C::VU, EPL = C::EPL, GP = C::GP, NG = C::NG;
@@ -321,12 +336,12 @@ __global__ __launch_bounds__((AttnCfg<T, D, G>::THREADS)) void attn_kernel(const
 #pragma unroll
                 for (int u = 0; u < 8; ++u) {
                     const int kc = min(base + quad * 8 + u, end - 1);
-                    kr[u] = (kc == new_slot ? knew_row : Krow + (size_t)kc * CH)[n16];
+                    kr[u] = ld_stream<NT>((kc == new_slot ? knew_row : Krow + (size_t)kc * CH) + n16);
                 }
 #pragma unroll
                 for (int u = 0; u < 8; ++u) {
                     const int kc = min(base + quad * 8 + u, end - 1);
-                    vr[u] = (kc == new_slot ? vnew_row : Vrow + (size_t)kc * CH)[n16];
+                    vr[u] = ld_stream<NT>((kc == new_slot ? vnew_row : Vrow + (size_t)kc * CH) + n16);
                 }
 #pragma unroll
                 for (int u = 0; u < 8; ++u) *reinterpret_cast<uint4*>(my_k + (quad * 8 + u) * KRS + n16 * 16) = kr[u];
@@ -745,7 +760,7 @@ static fk_status attn_launch(const fk_cache_desc* d, const AttnParams& base, int
             P.row_cnt = reinterpret_cast<uint32_t*>(ws);
             P.rec = nullptr;
             P.logit = reinterpret_cast<float*>(reinterpret_cast<char*>(ws) + attn_counter_bytes(d));
-            auto kern = attn_kernel<T, D, G, true>;
+            auto kern = attn_kernel<T, D, G, true, false>;
             static bool lds_ok[kMaxDevices] = {};  // per template instantiation
             if (!allow_dynamic_lds((const void*)kern, C::LDS_BYTES_FEAT, lds_ok)) return FK_ERR_LAUNCH;
             hipLaunchKernelGGL(kern, dim3(1, d->batch * d->n_kv_heads), dim3(C::THREADS), C::LDS_BYTES_FEAT, st, P);
@@ -759,7 +774,16 @@ static fk_status attn_launch(const fk_cache_desc* d, const AttnParams& base, int
     P.nsplit = p.nsplit;
     P.row_cnt = reinterpret_cast<uint32_t*>(ws);
     P.rec = reinterpret_cast<float*>(reinterpret_cast<char*>(ws) + attn_counter_bytes(d));
-    auto kern = attn_kernel<T, D, G, false>;
+    if constexpr (C::PVM) {
+        if ((size_t)rows * max_len * D * sizeof(T) * 2 >= kStreamNtBytes) {  // working set beyond the Infinity Cache
+            auto kern = attn_kernel<T, D, G, false, true>;
+            static bool lds_ok[kMaxDevices] = {};
+            if (!allow_dynamic_lds((const void*)kern, C::LDS_BYTES, lds_ok)) return FK_ERR_LAUNCH;
+            hipLaunchKernelGGL(kern, dim3(p.nsplit, rows), dim3(C::THREADS), C::LDS_BYTES, st, P);
+            return launch_status();
+        }
+    }
+    auto kern = attn_kernel<T, D, G, false, false>;
     static bool lds_ok[kMaxDevices] = {};  // per template instantiation
     if (!allow_dynamic_lds((const void*)kern, C::LDS_BYTES, lds_ok)) return FK_ERR_LAUNCH;
     hipLaunchKernelGGL(kern, dim3(p.nsplit, rows), dim3(C::THREADS), C::LDS_BYTES, st, P);
