@@ -255,7 +255,7 @@ fk_status fk_golden_trace(const float *alpha, int32_t n_kv_heads, int32_t T, int
 
 /*
  * Measurement helper, not part of the method: reads `bytes` (>= 16) of device memory at `src` with
- * 16-byte loads and discards them; `sink` is 4 bytes of device memory.  bench.py times it to report
+ * 16-byte loads (non-temporal from 352 MB on, like the attention kernel) and discards them; `sink` is 4 bytes of device memory.  bench.py times it to report
  * the achievable streaming bandwidth of the box beside the nominal HBM peak.
  */
 fk_status fk_stream_read(const void *src, size_t bytes, void *sink, void *stream);

@@ -19,25 +19,40 @@ extern "C" const char* fk_version(void) { return "fk 0.1 gfx950"; }
 // bandwidth that bench.py reports beside the nominal HBM peak
 // ---------------------------------------------------------------------------------------
 namespace fk {
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+template <bool NT>
+__device__ __forceinline__ uint32_t fold16(const uint4* p) {
+    if constexpr (NT) {
+        const u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p));
+        return v.x ^ v.y ^ v.z ^ v.w;
+    } else {
+        const uint4 v = *p;
+        return v.x ^ v.y ^ v.z ^ v.w;
+    }
+}
+// NT: non-temporal loads, the faster kind for buffers beyond the Infinity Cache (as in the attention kernel)
+template <bool NT>
 __global__ __launch_bounds__(256) void stream_read_kernel(const uint4* __restrict__ p, size_t n16, uint32_t* __restrict__ sink) {
     size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
     const size_t stride = (size_t)gridDim.x * blockDim.x;
     uint32_t acc = 0;
     for (; i + 3 * stride < n16; i += 4 * stride) {
-        const uint4 a = p[i], b = p[i + stride], c = p[i + 2 * stride], d = p[i + 3 * stride];
-        acc += a.x ^ a.y ^ a.z ^ a.w ^ b.x ^ b.y ^ b.z ^ b.w ^ c.x ^ c.y ^ c.z ^ c.w ^ d.x ^ d.y ^ d.z ^ d.w;
+        const uint32_t a = fold16<NT>(p + i), b = fold16<NT>(p + i + stride), c = fold16<NT>(p + i + 2 * stride),
+                       d = fold16<NT>(p + i + 3 * stride);
+        acc += a ^ b ^ c ^ d;
     }
-    for (; i < n16; i += stride) {
-        const uint4 a = p[i];
-        acc += a.x ^ a.y ^ a.z ^ a.w;
-    }
+    for (; i < n16; i += stride) acc += fold16<NT>(p + i);
     if (acc == 0x9e3779b9u) sink[0] = acc;  // keeps the loads alive; practically never true
 }
 }  // namespace fk
 
 extern "C" fk_status fk_stream_read(const void* src, size_t bytes, void* sink, void* stream) {
     if (!src || !sink || bytes < 16 || !fk::aligned16(src)) return FK_ERR_INVALID_ARG;
-    hipLaunchKernelGGL(fk::stream_read_kernel, dim3(4096), dim3(256), 0, (hipStream_t)stream, (const uint4*)src,
-                       bytes / 16, (uint32_t*)sink);
+    if (bytes >= ((size_t)352 << 20))
+        hipLaunchKernelGGL(fk::stream_read_kernel<true>, dim3(4096), dim3(256), 0, (hipStream_t)stream, (const uint4*)src,
+                           bytes / 16, (uint32_t*)sink);
+    else
+        hipLaunchKernelGGL(fk::stream_read_kernel<false>, dim3(4096), dim3(256), 0, (hipStream_t)stream, (const uint4*)src,
+                           bytes / 16, (uint32_t*)sink);
     return fk::launch_status();
 }

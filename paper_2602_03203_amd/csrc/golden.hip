@@ -16,6 +16,7 @@
 
 namespace fk {
 
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 static constexpr int kPoolThreads = 256;
 static constexpr int kPoolRowGroups = kPoolThreads / 16;  // rows covered by one load instruction of the workgroup
 static constexpr int kPoolU = 4;                          // loads in flight per thread
@@ -44,7 +45,9 @@ __global__ __launch_bounds__(kPoolThreads) void golden_pool_kernel(const T* __re
             for (int u = 0; u < kPoolU; ++u) {
                 const int r = min(r0 + u * kPoolRowGroups, total - 1);
                 const int h = r / rows, q = qs + r % rows;
-                v[u] = *reinterpret_cast<const uint4*>(base + ((size_t)h * Tn + q) * ld);
+                // read once, never again: non-temporal, so the lines do not push anything out of the caches
+                const u32x4 t4 = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(base + ((size_t)h * Tn + q) * ld));
+                v[u] = make_uint4(t4.x, t4.y, t4.z, t4.w);
             }
 #pragma unroll
             for (int u = 0; u < kPoolU; ++u) {
