@@ -258,6 +258,7 @@ def main():
     ap.add_argument("--features", action="store_true",
                     help="scorer inputs concat(k, v, attention features): the decode step also keeps the attention sums "
                          "(bf16, head_dim 128 only; the default run scores on k and v alone)")
+    ap.add_argument("--hidden", type=int, default=None, help="override the scorer's hidden width (the paper trains with 16)")
     ap.add_argument("--workload", choices=["decode", "golden"], default="decode",
                     help="decode: the budgeted decode + evict path (the headline); golden: the Golden Eviction label builder")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
@@ -280,6 +281,8 @@ def main():
         w = w.scaled(name=f"{w.name} (one layer of {w.layers})", layers=1)
     if args.prompt is not None:
         w = w.scaled(name=f"{w.name} (prompt {args.prompt})", prompt=args.prompt)
+    if args.hidden is not None:
+        w = w.scaled(name=f"{w.name} (scorer hidden {args.hidden})", hidden=args.hidden)
     K_steps = args.steps if args.steps is not None else w.steps
     W_steps = args.warmup
     n_gen = max(K_steps, W_steps)

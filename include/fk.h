@@ -67,7 +67,7 @@ typedef struct {
     const float *b1;  /* device [n_sets][hidden] */
     const float *w2;  /* device [n_sets][hidden] */
     const float *b2;  /* device [n_sets] */
-    int32_t hidden;   /* H; bf16: multiple of 32 with H*(2*head_dim+8)*2 + 8*H <= 160 KiB of LDS */
+    int32_t hidden;   /* H; bf16: multiple of 8 with H'*(2*head_dim+8)*2 + 8*H' <= 160 KiB of LDS, H' = H rounded up to 32 */
     int32_t per_head; /* 1: n_sets = n_kv_heads, one model per KV head; 0: one shared model */
     int32_t skip_len; /* rows with len[r] <= skip_len are skipped, their scores not written (pass the budget:
                          rows at or under budget are not pruned and need no scores); 0 scores every row */
@@ -203,7 +203,7 @@ fk_status fk_decode_step_feat(const fk_cache_desc *desc, const void *q, void *K,
  * fk_score_kv on x = concat(k, v, a) (Section 3.1 Eq. 1 with the attention features of Appendix
  * B.1).  scorer->w1 is [n_sets][2*head_dim + 6 g][hidden]; the fp32 features enter the contraction as
  * a bf16 head plus a bf16 remainder (16 significant bits; fp32 caches: plain fp32).  bf16: FK_ERR_UNSUPPORTED
- * unless hidden is a multiple of 32 and hidden * (2*head_dim + roundup(6 g, 16) + 8) * 2 + 8 * hidden <= 160 KiB.
+ * unless hidden is a multiple of 8 and H' * (2*head_dim + roundup(6 g, 16) + 8) * 2 + 8 * H' <= 160 KiB (H' = hidden rounded up to 32).
  */
 fk_status fk_score_kv_feat(const fk_cache_desc *desc, const void *K, const void *V, const float *feat,
                            const int32_t *len, int32_t max_len, const fk_scorer *scorer, float *scores,

@@ -88,8 +88,9 @@ __global__ __launch_bounds__(kScoreThreads) void score_mfma_kernel(
 
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     bf16_t* s_wt = reinterpret_cast<bf16_t*>(smem);
-    float* s_b1 = reinterpret_cast<float*>(smem + (size_t)H * FS * sizeof(bf16_t));
-    float* s_w2 = s_b1 + H;
+    const int HP = (H + 31) / 32 * 32;  // hidden units padded to whole MFMA tiles: zero weights, zero W2
+    float* s_b1 = reinterpret_cast<float*>(smem + (size_t)HP * FS * sizeof(bf16_t));
+    float* s_w2 = s_b1 + HP;
 
     // stage W1^T: a thread takes two consecutive features f, f+1 and 8 consecutive hidden
     // units, and writes 8 dwords (W1[f][j], W1[f+1][j]) to Wt[j][f..f+1]; consecutive lanes
@@ -116,9 +117,11 @@ __global__ __launch_bounds__(kScoreThreads) void score_mfma_kernel(
             for (int t = threadIdx.x; t < H * padw; t += kScoreThreads)
                 reinterpret_cast<uint32_t*>(s_wt)[((size_t)(t / padw) * FS + F) / 2 + t % padw] = 0u;
         }
-        for (int j = threadIdx.x; j < H; j += kScoreThreads) {
-            s_b1[j] = b1[(size_t)hw * H + j];
-            s_w2[j] = W2[(size_t)hw * H + j];
+        for (int t = threadIdx.x; t < (HP - H) * (FS / 2); t += kScoreThreads)  // the padding hidden units
+            reinterpret_cast<uint32_t*>(s_wt)[(size_t)H * (FS / 2) + t] = 0u;
+        for (int j = threadIdx.x; j < HP; j += kScoreThreads) {
+            s_b1[j] = j < H ? b1[(size_t)hw * H + j] : 0.f;
+            s_w2[j] = j < H ? W2[(size_t)hw * H + j] : 0.f;
         }
     }
     __syncthreads();
@@ -189,7 +192,7 @@ __global__ __launch_bounds__(kScoreThreads) void score_mfma_kernel(
 #pragma unroll
         for (int t = 0; t < NT; ++t) phi[t] = 0.f;
 
-        for (int ht = 0; ht < H / 32; ++ht) {
+        for (int ht = 0; ht < HP / 32; ++ht) {
             f32x16_t acc[NT];
 #pragma unroll
             for (int t = 0; t < NT; ++t)
@@ -321,7 +324,8 @@ __global__ __launch_bounds__(kSimpleWaves * kWave) void score_simple_kernel(
 // LDS of the MFMA kernel for group size gf of the feature part (0: no features)
 static size_t score_lds_bytes(int D, int H, int gf = 0) {
     const int fp = 2 * D + (kFeatPlanes * gf + 15) / 16 * 16;
-    return (size_t)H * (fp + kWPad) * 2 + (size_t)H * 8;
+    const int hp = (H + 31) / 32 * 32;
+    return (size_t)hp * (fp + kWPad) * 2 + (size_t)hp * 8;
 }
 
 template <int D, int GF>
@@ -377,7 +381,7 @@ extern "C" fk_status fk_score_kv(const fk_cache_desc* desc, const void* K, const
         if (D == 64) return score_simple_launch<float, 64>(desc, K, V, nullptr, len, max_len, scorer, scores, st);
         return score_simple_launch<float, 128>(desc, K, V, nullptr, len, max_len, scorer, scores, st);
     }
-    const bool mfma_ok = (H % 32 == 0) && score_lds_bytes(D, H) <= 160 * 1024;
+    const bool mfma_ok = (H % 8 == 0) && score_lds_bytes(D, H) <= 160 * 1024;
     if (!mfma_ok) return FK_ERR_UNSUPPORTED;
     if (D == 64) return score_mfma_launch<64, 0>(desc, K, V, nullptr, len, max_len, scorer, scores, st);
     return score_mfma_launch<128, 0>(desc, K, V, nullptr, len, max_len, scorer, scores, st);
@@ -398,7 +402,7 @@ extern "C" fk_status fk_score_kv_feat(const fk_cache_desc* desc, const void* K, 
         if (D == 64) return score_simple_launch<float, 64>(desc, K, V, feat, len, max_len, scorer, scores, st);
         return score_simple_launch<float, 128>(desc, K, V, feat, len, max_len, scorer, scores, st);
     }
-    if (H % 32 != 0 || score_lds_bytes(D, H, g) > 160 * 1024) return FK_ERR_UNSUPPORTED;
+    if (H % 8 != 0 || score_lds_bytes(D, H, g) > 160 * 1024) return FK_ERR_UNSUPPORTED;
 #define FK_SCORE_FEAT_CASE(GG)                                                                              \
     case GG:                                                                                                \
         return D == 64 ? score_mfma_launch<64, GG>(desc, K, V, feat, len, max_len, scorer, scores, st)      \

@@ -69,9 +69,9 @@ def test_argument_validation_without_gpu(fklib):
     assert need > 0
     assert L.fk_decode_attn(ctypes.byref(good), p, p, p, p, 512, 1.0, p, p, need - 1, 0) == fklib.FK_ERR_WORKSPACE
     assert L.fk_decode_attn(ctypes.byref(good), p, p, p, p, 512, 1.0, p, 0, 0, 0) == fklib.FK_ERR_WORKSPACE
-    # scorer: hidden not a multiple of 32 in bf16 is unsupported; null weights invalid
+    # scorer: hidden not a multiple of 8 in bf16 is unsupported; null weights invalid
     S = fklib.fk_scorer
-    assert L.fk_score_kv(ctypes.byref(good), p, p, p, 512, ctypes.byref(S(p, p, p, p, 48, 1)), p, 0) == fklib.FK_ERR_UNSUPPORTED
+    assert L.fk_score_kv(ctypes.byref(good), p, p, p, 512, ctypes.byref(S(p, p, p, p, 44, 1)), p, 0) == fklib.FK_ERR_UNSUPPORTED
     assert L.fk_score_kv(ctypes.byref(good), p, p, p, 512, ctypes.byref(S(0, p, p, p, 64, 1)), p, 0) == fklib.FK_ERR_INVALID_ARG
     assert L.fk_score_kv(ctypes.byref(good), p, p, p, 512, ctypes.byref(S(p, p, p, p, 4096, 1)), p, 0) == fklib.FK_ERR_UNSUPPORTED
 
@@ -97,7 +97,7 @@ def test_argument_validation_of_the_next_row_calls(fklib):
     assert L.fk_decode_step_feat(ctypes.byref(good), *args, 512, 1.0, p, 0, 128, p, p, need - 1, 0) == fklib.FK_ERR_WORKSPACE
     S = fklib.fk_scorer
     assert L.fk_score_kv_feat(ctypes.byref(good), p, p, 0, p, 512, ctypes.byref(S(p, p, p, p, 64, 1)), p, 0) == fklib.FK_ERR_INVALID_ARG
-    assert L.fk_score_kv_feat(ctypes.byref(good), p, p, p, p, 512, ctypes.byref(S(p, p, p, p, 48, 1)), p, 0) == fklib.FK_ERR_UNSUPPORTED
+    assert L.fk_score_kv_feat(ctypes.byref(good), p, p, p, p, 512, ctypes.byref(S(p, p, p, p, 44, 1)), p, 0) == fklib.FK_ERR_UNSUPPORTED
     assert L.fk_compact_feat(ctypes.byref(good), p, p, p, 0, p, p, 256, 0) == fklib.FK_ERR_INVALID_ARG
     assert L.fk_compact_feat(ctypes.byref(good), p, p, p, p, p, p, 513, 0) == fklib.FK_ERR_INVALID_ARG
     # Golden Eviction

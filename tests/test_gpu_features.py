@@ -197,8 +197,8 @@ def test_bad_arguments_are_refused(gpu):
     with pytest.raises(fk.FkError) as e:
         fk.fk_decode_step_feat(d, z, z, z, i, i, z, z, i, 8, 1.0, f, 0, 4, z, ws[:64])   # workspace too small
     assert e.value.code == 3
-    W1 = torch.zeros((1, 2 * 128 + 24, 48), dtype=torch.bfloat16, device="cuda")         # hidden not a multiple of 32
-    b = torch.zeros((1, 48), dtype=torch.float32, device="cuda")
+    W1 = torch.zeros((1, 2 * 128 + 24, 44), dtype=torch.bfloat16, device="cuda")         # hidden not a multiple of 8
+    b = torch.zeros((1, 44), dtype=torch.float32, device="cuda")
     sc = torch.zeros((1, 1, 64), dtype=torch.float32, device="cuda")
     with pytest.raises(fk.FkError) as e:
         fk.fk_score_kv_feat(d, z, z, f, i, 8, W1, b, b, b[:, 0].contiguous(), sc)

@@ -117,6 +117,8 @@ SCORE_SHAPES = [
     ("bf16", 128, 32, 2, 100, [100, 64], False),       # shared weights, narrow hidden
     ("bf16", 64, 96, 3, 130, [130, 65], True),
     ("f32", 128, 20, 1, 70, [70], True),
+    ("bf16", 128, 16, 8, 2176, [2176, 1500], True),    # the paper's hidden width (Section 4.1): padded to one MFMA tile
+    ("bf16", 128, 48, 2, 300, [300, 31], True),        # a width that is no multiple of 32
 ]
 
 
