@@ -246,6 +246,112 @@ def bench_golden(args):
     print(json.dumps(result), flush=True)
 
 
+def bench_stack(args, w: si.Workload):
+    """Whole layer stack of a multi-layer configuration (--stack): every decode step runs the fused append +
+    attention of EVERY layer, every L-th step the eviction event of every layer; every layer has its own cache,
+    lengths and scorer weights.  The run starts near the steady state (prompt = budget - L/2 unless --prompt) and
+    its inputs are drawn on the device with seeded torch ops in the distributions of the configuration
+    (N(0,1)/sqrt(D), 1 % of the positions with 3x key norm); step inputs cycle through a pool of 64."""
+    import torch
+    import paper_2602_03203_amd as fk
+    fk.lib()
+    torch.cuda.set_device(0)
+    NL, Bt, Hq, Hkv, D, B, L, cap = w.layers, w.batch, w.n_q_heads, w.n_kv_heads, w.head_dim, w.budget, w.interval, w.capacity
+    P0 = args.prompt if args.prompt is not None else B - L // 2
+    K_steps = args.steps if args.steps is not None else 2 * L
+    W_steps = min(args.warmup, L)
+    dt = torch.bfloat16 if w.dtype == "bf16" else torch.float32
+    gen = torch.Generator(device="cuda").manual_seed(w.seed % (2 ** 31))
+    sd = 1.0 / np.sqrt(D)
+    K0 = torch.empty((NL, Bt, Hkv, cap, D), dtype=dt, device="cuda")
+    V0 = torch.empty_like(K0)
+    for l in range(NL):
+        heavy = 1.0 + 2.0 * (torch.rand((Bt, 1, cap, 1), generator=gen, device="cuda") < 0.01).float()
+        K0[l] = (torch.randn((Bt, Hkv, cap, D), generator=gen, device="cuda") * sd * heavy).to(dt)
+        V0[l] = (torch.randn((Bt, Hkv, cap, D), generator=gen, device="cuda") * sd).to(dt)
+    pos0 = torch.arange(cap, dtype=torch.int32, device="cuda").expand(NL, Bt, Hkv, cap).contiguous()
+    len0 = torch.full((NL, Bt, Hkv), P0, dtype=torch.int32, device="cuda")
+    NP = 64
+    dq = (torch.randn((NP, Bt, Hq, D), generator=gen, device="cuda") * sd).to(dt)
+    dk = (torch.randn((NP, Bt, Hkv, D), generator=gen, device="cuda") * sd).to(dt)
+    dv = (torch.randn((NP, Bt, Hkv, D), generator=gen, device="cuda") * sd).to(dt)
+    F, H = 2 * D, w.hidden
+    W1 = (torch.randn((NL, Hkv, F, H), generator=gen, device="cuda") / np.sqrt(F)).to(dt)
+    b1 = torch.randn((NL, Hkv, H), generator=gen, device="cuda") / np.sqrt(F)
+    W2 = torch.randn((NL, Hkv, H), generator=gen, device="cuda") / np.sqrt(H)
+    b2 = torch.randn((NL, Hkv), generator=gen, device="cuda") / np.sqrt(H)
+    desc = fk.CacheDesc(Bt, Hq, Hkv, D, cap, w.dtype, cold=NL * Bt * Hkv * cap * D * 2 * w.elem_bytes > (256 << 20))
+    Kc, Vc, posc, lenc = (torch.empty_like(x) for x in (K0, V0, pos0, len0))
+    ws = fk.new_attn_workspace(desc)
+    out = torch.empty((Bt, Hq, D), dtype=dt, device="cuda")
+    scores = torch.zeros((Bt, Hkv, cap), dtype=torch.float32, device="cuda")
+    keep = torch.zeros((Bt, Hkv, B), dtype=torch.int32, device="cuda")
+    dp = torch.zeros((Bt,), dtype=torch.int32, device="cuda")
+    stream = torch.cuda.current_stream()
+    scale = w.softmax_scale
+    n_tot = max(K_steps, W_steps)
+    lens = np.empty(n_tot, np.int64)     # cache length at the attention of step t (all rows alike)
+    cur = P0
+    for t in range(n_tot):
+        cur += 1
+        lens[t] = cur
+        if (t + 1) % L == 0:
+            cur = min(cur, B)
+
+    def reset():
+        Kc.copy_(K0); Vc.copy_(V0); posc.copy_(pos0); lenc.copy_(len0)
+
+    def run(n_steps, brackets=None):
+        for t in range(n_steps):
+            ml = int(min(lens[t], cap))
+            dp.fill_(P0 + t)
+            if brackets is not None:
+                brackets[t][0].record(stream)
+            for l in range(NL):
+                fk.fk_decode_step(desc, dq[(t + l) % NP], Kc[l], Vc[l], posc[l], lenc[l], dk[(t + 3 * l) % NP], dv[(t + 5 * l) % NP],
+                                  dp, ml, scale, out, ws, stream)
+            if brackets is not None:
+                brackets[t][1].record(stream)
+            if (t + 1) % L == 0:
+                for l in range(NL):
+                    fk.fk_score_kv(desc, Kc[l], Vc[l], lenc[l], ml, W1[l], b1[l], W2[l], b2[l], scores, stream, skip_len=B)
+                    fk.fk_select_keep(desc, scores, posc[l], lenc[l], ml, B, L, keep, stream)
+                    fk.fk_compact(desc, Kc[l], Vc[l], posc[l], lenc[l], keep, B, stream)
+
+    reset()
+    run(W_steps)
+    torch.cuda.synchronize()
+    reset()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    run(K_steps)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    fl = lenc.cpu().numpy()
+    assert (fl == fl.flat[0]).all() and fl.flat[0] == (min(lens[K_steps - 1], B) if K_steps % L == 0 else lens[K_steps - 1])
+    e = w.elem_bytes
+    step_bytes = [NL * (Bt * Hkv * int(lens[t]) * D * 2 * e + Bt * Hq * D * 2 * e) for t in range(K_steps)]
+    result = {
+        "metric": "decode tokens/s, budgeted KV decode+evict (attention + scorer + top-k + compaction), whole layer stack",
+        "value": Bt * K_steps / wall, "unit": "tokens/s", "n_gpus": 1, "steps": K_steps, "warmup": W_steps,
+        "ms_per_step": 1e3 * wall / K_steps, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": w.dtype, "data": "synthetic (drawn on the device)",
+        "config": {"workload": f"{w.name} (all {NL} layers, prompt {P0})", "layers": NL, "batch": Bt, "n_q_heads": Hq,
+                   "n_kv_heads": Hkv, "head_dim": D, "budget": B, "eviction_interval": L, "capacity": cap, "scorer_hidden": H},
+        "path_gbs_algorithmic": sum(step_bytes) / wall / 1e9,
+    }
+    reset()
+    br = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(K_steps)]
+    run(K_steps, br)
+    torch.cuda.synchronize()
+    ms = sum(a.elapsed_time(b) for a, b in br)
+    achieved = sum(step_bytes) / (ms * 1e-3) / 1e9
+    result["roofline"] = {"kernel": "attn_kernel (fk_decode_step), all layers of a step between one pair of HIP events", "bound": "hbm",
+                          "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                          "avg_launch_us": ms * 1e3 / (K_steps * NL), "algorithmic_bytes_per_launch": sum(step_bytes) / (K_steps * NL)}
+    print(json.dumps(result), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -258,6 +364,7 @@ def main():
     ap.add_argument("--features", action="store_true",
                     help="scorer inputs concat(k, v, attention features): the decode step also keeps the attention sums "
                          "(bf16, head_dim 128 only; the default run scores on k and v alone)")
+    ap.add_argument("--stack", action="store_true", help="multi-layer configurations: run every layer at every step")
     ap.add_argument("--hidden", type=int, default=None, help="override the scorer's hidden width (the paper trains with 16)")
     ap.add_argument("--workload", choices=["decode", "golden"], default="decode",
                     help="decode: the budgeted decode + evict path (the headline); golden: the Golden Eviction label builder")
@@ -277,7 +384,11 @@ def main():
     host_threads = min(16, os.cpu_count() or 1)
 
     w = si.config(args.config)
-    if w.layers != 1:   # stacks: every layer runs the same kernels on its own cache; one layer is timed
+    if w.layers != 1 and args.stack:
+        if args.hidden is not None:
+            w = w.scaled(hidden=args.hidden)
+        return bench_stack(args, w)
+    if w.layers != 1:   # stacks: every layer runs the same kernels on its own cache; without --stack one layer is timed
         w = w.scaled(name=f"{w.name} (one layer of {w.layers})", layers=1)
     if args.prompt is not None:
         w = w.scaled(name=f"{w.name} (prompt {args.prompt})", prompt=args.prompt)

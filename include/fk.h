@@ -59,7 +59,14 @@ typedef struct {
     int32_t head_dim;   /* D */
     int32_t capacity;   /* slots per row, >= B + L */
     int32_t dtype;      /* fk_dtype of q, K, V, out and of the scorer's W1 */
+    int32_t flags;      /* FK_CACHE_* bits, 0 by default */
 } fk_cache_desc;
+
+/* The cache is not expected to sit in the GPU's caches when a call starts (one layer of a deep stack whose
+ * layers are visited in turn): attention streams K and V with non-temporal loads whatever their size.  Without
+ * the flag that is done from 352 MB of K + V per call on, below which a cache re-read every step stays in the
+ * Infinity Cache.  A hint: results do not depend on it. */
+#define FK_CACHE_COLD 1
 
 /* Scoring model of one layer (Appendix B.1): phi = gelu(x W1 + b1) W2 + b2, x = concat(k, v). */
 typedef struct {

@@ -27,7 +27,7 @@ SYMBOLS = ["fk_status_string", "fk_version", "fk_append", "fk_decode_attn_worksp
 
 class fk_cache_desc(ctypes.Structure):
     _fields_ = [("batch", ctypes.c_int32), ("n_q_heads", ctypes.c_int32), ("n_kv_heads", ctypes.c_int32),
-                ("head_dim", ctypes.c_int32), ("capacity", ctypes.c_int32), ("dtype", ctypes.c_int32)]
+                ("head_dim", ctypes.c_int32), ("capacity", ctypes.c_int32), ("dtype", ctypes.c_int32), ("flags", ctypes.c_int32)]
 
 
 class fk_scorer(ctypes.Structure):
@@ -108,10 +108,11 @@ class CacheDesc:
     head_dim: int
     capacity: int
     dtype: str  # 'f32' | 'bf16'
+    cold: bool = False  # FK_CACHE_COLD: the cache is not cache resident between calls (a layer of a deep stack)
 
     def c(self) -> fk_cache_desc:
         return fk_cache_desc(self.batch, self.n_q_heads, self.n_kv_heads, self.head_dim, self.capacity,
-                             FK_F32 if self.dtype == "f32" else FK_BF16)
+                             FK_F32 if self.dtype == "f32" else FK_BF16, 1 if self.cold else 0)
 
     @property
     def torch_dtype(self):

@@ -775,7 +775,7 @@ static fk_status attn_launch(const fk_cache_desc* d, const AttnParams& base, int
     P.row_cnt = reinterpret_cast<uint32_t*>(ws);
     P.rec = reinterpret_cast<float*>(reinterpret_cast<char*>(ws) + attn_counter_bytes(d));
     if constexpr (C::PVM) {
-        if ((size_t)rows * max_len * D * sizeof(T) * 2 >= kStreamNtBytes) {  // working set beyond the Infinity Cache
+        if ((d->flags & FK_CACHE_COLD) || (size_t)rows * max_len * D * sizeof(T) * 2 >= kStreamNtBytes) {  // not cache resident
             auto kern = attn_kernel<T, D, G, false, true>;
             static bool lds_ok[kMaxDevices] = {};
             if (!allow_dynamic_lds((const void*)kern, C::LDS_BYTES, lds_ok)) return FK_ERR_LAUNCH;

@@ -48,6 +48,11 @@ def test_decode_attn_matches_oracle(gpu, ora, dtype, D, Hq, Hkv, cap, lens):
     # a tighter max_len hint that still covers every row gives the same answer
     got = dev.attn(qd, D ** -0.5, max_len=max(max(lens), 1))
     gpu.assert_attn_close(got, ora.decode_attn(c, q, D ** -0.5), dtype, "max_len hint")
+    # the "cold cache" hint changes how K and V are fetched, not a bit of the result
+    plain = dev.attn(qd, D ** -0.5)
+    dev.desc.cold = True
+    assert np.array_equal(dev.attn(qd, D ** -0.5), plain)
+    dev.desc.cold = False
     # a hint that is too small only costs time: the last split runs on to the end of the row
     for hint in (1, 33, max(max(lens) // 3, 1)):
         got = dev.attn(qd, D ** -0.5, max_len=hint)
