@@ -65,7 +65,8 @@ typedef struct {
 /* The cache is not expected to sit in the GPU's caches when a call starts (one layer of a deep stack whose
  * layers are visited in turn): attention streams K and V with non-temporal loads whatever their size.  Without
  * the flag that is done from 352 MB of K + V per call on, below which a cache re-read every step stays in the
- * Infinity Cache.  A hint: results do not depend on it. */
+ * Infinity Cache, and rows may be cut into more splits (size the workspace with the same descriptor).  A hint:
+ * results are the same up to the order of the floating-point merges. */
 #define FK_CACHE_COLD 1
 
 /* Scoring model of one layer (Appendix B.1): phi = gelu(x W1 + b1) W2 + b2, x = concat(k, v). */

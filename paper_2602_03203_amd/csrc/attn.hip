@@ -118,6 +118,10 @@ struct AttnPlan {
 // cross-workgroup merge at the end of the launch); the other kernels want about two per CU.
 static int attn_max_splits(const fk_cache_desc* d) {
     const int rows = d->batch * d->n_kv_heads;
+    if (d->dtype == FK_BF16 && d->head_dim == 128 && (d->flags & FK_CACHE_COLD)) {
+        const int want = 256 / rows;  // a cold cache comes from HBM, whose latency takes every CU to cover: up to 256 workgroups
+        return want < 1 ? 1 : want;
+    }
     const int target = (d->dtype == FK_BF16 && d->head_dim == 128) ? 128 : 512;
     const int want = (target + rows - 1) / rows;
     return want < 1 ? 1 : want;

@@ -35,6 +35,7 @@ ATTN_SHAPES = [
 
 @pytest.mark.parametrize("dtype,D,Hq,Hkv,cap,lens", ATTN_SHAPES)
 def test_decode_attn_matches_oracle(gpu, ora, dtype, D, Hq, Hkv, cap, lens):
+    import paper_2602_03203_amd as fk
     Bt = len(lens)
     print(f"attn case {dtype} D={D} Hq={Hq} Hkv={Hkv} cap={cap} lens={lens}", flush=True)
     c = random_cache(ora, 1000 + D + Hq, dtype, Bt, Hkv, cap, D, lens=lens)
@@ -51,8 +52,12 @@ def test_decode_attn_matches_oracle(gpu, ora, dtype, D, Hq, Hkv, cap, lens):
     # the "cold cache" hint changes how K and V are fetched, not a bit of the result
     plain = dev.attn(qd, D ** -0.5)
     dev.desc.cold = True
-    assert np.array_equal(dev.attn(qd, D ** -0.5), plain)
-    dev.desc.cold = False
+    ws_small, dev.ws = dev.ws, fk.new_attn_workspace(dev.desc)     # a cold cache may be cut into more splits
+    cold = dev.attn(qd, D ** -0.5)
+    gpu.assert_attn_close(cold, ora.decode_attn(c, q, D ** -0.5), dtype, "cold-cache hint")
+    if Bt * Hkv >= 128 or dtype != "bf16" or D != 128:
+        assert np.array_equal(cold, plain)                          # same splits: the same bits
+    dev.desc.cold, dev.ws = False, ws_small
     # a hint that is too small only costs time: the last split runs on to the end of the row
     for hint in (1, 33, max(max(lens) // 3, 1)):
         got = dev.attn(qd, D ** -0.5, max_len=hint)
