@@ -372,7 +372,7 @@ def main():
     ap.add_argument("--no-kernel-timing", action="store_true", help="skip the HIP-event pass over the attention launches")
     args = ap.parse_args()
     if args.gpus != 1:
-        sys.exit("bench.py: this build runs on ONE GPU (rows are independent; see DESIGN.md for how it would shard); use --gpus 1")
+        sys.exit("bench.py: this build runs on ONE GPU (rows are independent: batch or KV-head sharding needs no exchange inside this path); use --gpus 1")
 
     if args.workload == "golden":
         return bench_golden(args)
