@@ -333,3 +333,87 @@ def test_append_bit_exact(gpu, ora, dtype, D):
             host.K[b], host.V[b], host.pos[b], host.len[b] = sub.K[0], sub.V[0], sub.pos[0], sub.len[0]
     assert np.array_equal(got.len, host.len) and np.array_equal(got.pos, host.pos)
     assert np.array_equal(got.K, host.K) and np.array_equal(got.V, host.V)
+
+
+def test_select_and_compact_random_shapes(gpu, ora):
+    """Forty seeded random shapes (capacity, lengths, budget, protected tail, tie density, candidate count):
+    both selection policies and the compaction they feed, bit for bit against the oracle.  The draws favour the
+    boundaries: len = budget + 1, recent = 0 or = budget, budget = capacity, n_cand around the number evicted."""
+    import paper_2602_03203_amd as fk
+    rng = np.random.default_rng(20260203)
+    for case in range(40):
+        Bt, Hkv = int(rng.integers(1, 4)), int(rng.integers(1, 4))
+        cap = int(rng.choice([33, 64, 257, 1000, 1025, 2049, 3000]))
+        budget = int(rng.choice([1, cap // 3 + 1, cap // 2, cap - 1, cap]))
+        recent = int(rng.choice([0, 1, budget // 2, budget]))
+        lens = [int(rng.choice([0, 1, budget, min(budget + 1, cap), cap, int(rng.integers(0, cap + 1))])) for _ in range(Bt)]
+        ties = int(rng.choice([0, 2, 5]))
+        n_cand = int(rng.choice([0, 1, max(cap - budget, 1), 2 * max(cap - budget, 1), cap]))
+        D, dtype = (64, "f32") if case % 2 else (128, "bf16")
+        print(f"random case {case}: Bt={Bt} Hkv={Hkv} cap={cap} lens={lens} B={budget} R={recent} ties={ties} K'={n_cand} {dtype}", flush=True)
+        c = random_cache(ora, 7000 + case, dtype, Bt, Hkv, cap, D, lens=lens)
+        sc = si.gen_scores(7100 + case, (Bt, Hkv, cap), ties=ties)
+        noise = si.gen_gumbel(7200 + case, (Bt, Hkv, cap), event=case, levels=ties)
+        dev = gpu.DevCache(c, Hkv)
+        dsc, dnz = gpu.to_dev(sc), gpu.to_dev(noise)
+        keep = torch.full((Bt, Hkv, budget), -1, dtype=torch.int32, device="cuda")
+        fk.fk_select_keep_sampled(dev.desc, dsc, dnz, dev.pos, dev.len, cap, budget, recent, n_cand, keep)
+        ref_s = ora.select_keep_sampled(sc, noise, c.pos, c.len, budget, recent, n_cand)
+        fk.fk_select_keep(dev.desc, dsc, dev.pos, dev.len, cap, budget, recent, keep)
+        ref = ora.select_keep(sc, c.pos, c.len, budget, recent, "sort")
+        got = keep.cpu().numpy()
+        for b in range(Bt):
+            n = lens[b]
+            m = budget if n > budget else n          # rows at or under budget: identity over the live slots
+            assert np.array_equal(got[b, :, :m], ref[b, :, :m]), f"case {case} row {b}"
+        fk.fk_select_keep_sampled(dev.desc, dsc, dnz, dev.pos, dev.len, cap, budget, recent, n_cand, keep)
+        got_s = keep.cpu().numpy()
+        for b in range(Bt):
+            m = budget if lens[b] > budget else lens[b]
+            assert np.array_equal(got_s[b, :, :m], ref_s[b, :, :m]), f"case {case} row {b} (sampled)"
+        fk.fk_compact(dev.desc, dev.K, dev.V, dev.pos, dev.len, keep, budget)
+        ora.compact(c, ref_s, budget)
+        host = dev.host(ora)
+        assert np.array_equal(host.len, c.len)
+        for b in range(Bt):
+            m = int(c.len[b])
+            assert np.array_equal(host.pos[b, :, :m], c.pos[b, :, :m])
+            assert np.array_equal(host.K[b, :, :m], c.K[b, :, :m]) and np.array_equal(host.V[b, :, :m], c.V[b, :, :m])
+
+
+def test_attention_and_fused_step_random_shapes(gpu, ora):
+    """Thirty seeded random shapes: every group size 1 .. 8, both head sizes and storage types, lengths around
+    the 32-key tile and the split boundaries (0, 1, 31 .. 33, capacity - 1, capacity), random max_len hints;
+    attention and the fused append + attention step against the oracle."""
+    import paper_2602_03203_amd as fk
+    rng = np.random.default_rng(26020302)
+    for case in range(30):
+        g = int(rng.integers(1, 9))
+        Hkv, Bt = int(rng.integers(1, 4)), int(rng.integers(1, 4))
+        D, dtype = (64, 128)[case % 2], ("bf16", "f32")[(case // 2) % 2]
+        cap = int(rng.choice([34, 65, 130, 513, 1500]))
+        choices = [0, 1, 31, 32, 33, cap - 1, cap, int(rng.integers(0, cap + 1))]
+        lens = [int(rng.choice(choices)) for _ in range(Bt)]
+        scale = float(rng.choice([D ** -0.5, 0.02, 2.0 * D ** -0.5]))
+        print(f"random attn case {case}: {dtype} D={D} g={g} Hkv={Hkv} cap={cap} lens={lens} scale={scale:.3f}", flush=True)
+        c = random_cache(ora, 8000 + case, dtype, Bt, Hkv, cap, D, lens=lens)
+        q = random_q(8100 + case, dtype, Bt, Hkv * g, D)
+        dev = gpu.DevCache(c, Hkv * g)
+        qd = gpu.to_dev(q)
+        hint = int(rng.choice([cap, max(max(lens), 1), max(max(lens) // 2, 1)]))
+        gpu.assert_attn_close(dev.attn(qd, scale, max_len=hint), ora.decode_attn(c, q, scale), dtype, f"case {case}")
+        # fused step: rows at capacity are left alone, the others grow by one
+        kn, vn = random_q(8200 + case, dtype, Bt, Hkv, D), random_q(8300 + case, dtype, Bt, Hkv, D)
+        pn = np.array([3 * cap + 7 + b for b in range(Bt)], np.int32)
+        fk.fk_decode_step(dev.desc, qd, dev.K, dev.V, dev.pos, dev.len, gpu.to_dev(kn), gpu.to_dev(vn), gpu.to_dev(pn),
+                          min(max(lens) + 1, cap), scale, dev.out, dev.ws)
+        for b in range(Bt):      # the oracle refuses a full row; the device leaves it alone
+            if c.len[b] < cap:
+                ora.append(ora.Cache(dtype, c.K[b:b + 1], c.V[b:b + 1], c.pos[b:b + 1], c.len[b:b + 1]), kn[b:b + 1], vn[b:b + 1], pn[b:b + 1])
+        gpu.assert_attn_close(gpu.out_to_f64(dev.out), ora.decode_attn(c, q, scale), dtype, f"case {case} fused")
+        host = dev.host(ora)
+        assert np.array_equal(host.len, c.len)
+        for b in range(Bt):
+            m = int(c.len[b])
+            assert np.array_equal(host.pos[b, :, :m], c.pos[b, :, :m]) and np.array_equal(host.K[b, :, :m], c.K[b, :, :m])
+            assert np.array_equal(host.V[b, :, :m], c.V[b, :, :m])
