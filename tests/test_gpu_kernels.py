@@ -417,3 +417,31 @@ def test_attention_and_fused_step_random_shapes(gpu, ora):
             m = int(c.len[b])
             assert np.array_equal(host.pos[b, :, :m], c.pos[b, :, :m]) and np.array_equal(host.K[b, :, :m], c.K[b, :, :m])
             assert np.array_equal(host.V[b, :, :m], c.V[b, :, :m])
+
+
+def test_scorer_random_shapes(gpu, ora):
+    """Twenty seeded random scorer shapes: hidden widths that are and are not multiples of 32, shared and
+    per-head weights, both head sizes and storage types, lengths around the 32-pair tile."""
+    import paper_2602_03203_amd as fk
+    rng = np.random.default_rng(26020303)
+    for case in range(20):
+        D, dtype = (64, 128)[case % 2], ("bf16", "f32")[(case // 2) % 2]
+        H = int(rng.choice([8, 16, 24, 40, 64, 72, 128, 200, 256])) if dtype == "bf16" else int(rng.choice([1, 5, 16, 63, 64, 65, 130]))
+        Hkv, Bt = int(rng.integers(1, 5)), int(rng.integers(1, 4))
+        per_head = bool(rng.integers(0, 2)) or Hkv == 1
+        cap = int(rng.choice([33, 100, 520, 1100]))
+        lens = [int(rng.choice([0, 1, 31, 32, 33, cap, int(rng.integers(0, cap + 1))])) for _ in range(Bt)]
+        print(f"random score case {case}: {dtype} D={D} H={H} Hkv={Hkv} per_head={per_head} cap={cap} lens={lens}", flush=True)
+        c = random_cache(ora, 9000 + case, dtype, Bt, Hkv, cap, D, lens=lens, scale=0.5)
+        nset, F = (Hkv if per_head else 1), 2 * D
+        W1 = store((si.normal(9100 + case, si.T_W1, 0, np.arange(nset * F * H)).reshape(nset, F, H) / np.sqrt(F)).astype(np.float32), dtype)
+        b1 = (si.normal(9100 + case, si.T_B1, 0, np.arange(nset * H)).reshape(nset, H) * 0.2).astype(np.float32)
+        W2 = (si.normal(9100 + case, si.T_W2, 0, np.arange(nset * H)).reshape(nset, H) / np.sqrt(H)).astype(np.float32)
+        b2 = (si.normal(9100 + case, si.T_B2, 0, np.arange(nset)) * 0.3).astype(np.float32)
+        ref = ora.score_kv(c, W1, b1, W2, b2)
+        dev = gpu.DevCache(c, Hkv)
+        fk.fk_score_kv(dev.desc, dev.K, dev.V, dev.len, cap, gpu.to_dev(W1), gpu.to_dev(b1), gpu.to_dev(W2), gpu.to_dev(b2), dev.scores)
+        got = dev.scores.cpu().numpy()
+        gpu.assert_scores_close(got, ref, lens, f"case {case}")
+        for b in range(Bt):
+            assert np.isnan(got[b, :, lens[b]:]).all()
