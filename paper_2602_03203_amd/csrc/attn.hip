@@ -764,10 +764,20 @@ static fk_status attn_launch(const fk_cache_desc* d, const AttnParams& base, int
             P.row_cnt = reinterpret_cast<uint32_t*>(ws);
             P.rec = nullptr;
             P.logit = reinterpret_cast<float*>(reinterpret_cast<char*>(ws) + attn_counter_bytes(d));
+            const int frows = d->batch * d->n_kv_heads;
+            if constexpr (C::PVM) {
+                if ((d->flags & FK_CACHE_COLD) || (size_t)frows * max_len * D * sizeof(T) * 2 >= kStreamNtBytes) {
+                    auto kern = attn_kernel<T, D, G, true, true>;
+                    static bool lds_ok[kMaxDevices] = {};
+                    if (!allow_dynamic_lds((const void*)kern, C::LDS_BYTES_FEAT, lds_ok)) return FK_ERR_LAUNCH;
+                    hipLaunchKernelGGL(kern, dim3(1, frows), dim3(C::THREADS), C::LDS_BYTES_FEAT, st, P);
+                    return launch_status();
+                }
+            }
             auto kern = attn_kernel<T, D, G, true, false>;
             static bool lds_ok[kMaxDevices] = {};  // per template instantiation
             if (!allow_dynamic_lds((const void*)kern, C::LDS_BYTES_FEAT, lds_ok)) return FK_ERR_LAUNCH;
-            hipLaunchKernelGGL(kern, dim3(1, d->batch * d->n_kv_heads), dim3(C::THREADS), C::LDS_BYTES_FEAT, st, P);
+            hipLaunchKernelGGL(kern, dim3(1, frows), dim3(C::THREADS), C::LDS_BYTES_FEAT, st, P);
             return launch_status();
         }
     }

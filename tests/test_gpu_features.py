@@ -41,7 +41,7 @@ def assert_feat_close(got, ref, what):
     assert (err <= 0).all(), f"{what}: worst excess {err.max():.3e} at {np.unravel_index(err.argmax(), err.shape)}"
 
 
-def lockstep_feat(gpu, ora, w, n_steps, sample_rows=None, scale=None, check_every=1):
+def lockstep_feat(gpu, ora, w, n_steps, sample_rows=None, scale=None, check_every=1, cold=False):
     import paper_2602_03203_amd as fk
     scale = w.softmax_scale if scale is None else scale
     lens0 = si.initial_lengths(w)
@@ -49,6 +49,7 @@ def lockstep_feat(gpu, ora, w, n_steps, sample_rows=None, scale=None, check_ever
     print(f"lockstep_feat {w.name}: g={g} B={B} L={L}", flush=True)
     full = workload_cache(ora, w)
     dev = gpu.DevCache(full, w.n_q_heads)
+    dev.desc.cold = cold
     feat = fk.new_feat(dev.desc)
     fws = fk.new_feat_workspace(dev.desc)
     W1, b1, W2, b2 = si.gen_scorer_feat(w, 0)
@@ -145,6 +146,12 @@ def test_events_on_rows_still_under_budget(gpu, ora):
     """Short prompt: the first two events find every row under budget (the chunk is closed, nothing moves)."""
     w = small(4, prompt=60)
     assert lockstep_feat(gpu, ora, w, 260) == 4
+
+
+def test_cold_cache_hint(gpu, ora):
+    """The cold-cache flag (non-temporal K / V loads) on the feature path: same parity."""
+    assert lockstep_feat(gpu, ora, small(4), 150, cold=True) == 2
+    assert lockstep_feat(gpu, ora, small(7), 70, cold=True) == 1
 
 
 def test_interval_shorter_than_the_windows(gpu, ora):
