@@ -79,36 +79,6 @@ def gen_prompt(w: si.Workload, lens0: np.ndarray, threads: int):
     return K, V, pos
 
 
-def len_schedule(w: si.Workload, lens0: np.ndarray, n_steps: int):
-    """Host replay of the protocol's cache sizes: lens_at_attn [T, Bt] (after the append of step t)."""
-    lens = lens0.astype(np.int64).copy()
-    out = np.empty((n_steps, w.batch), np.int64)
-    ev = []
-    for t in range(n_steps):
-        lens += 1
-        out[t] = lens
-        if (t + 1) % w.interval == 0:
-            ev.append(lens.copy())
-            lens = np.minimum(lens, w.budget)
-    return out, ev
-
-
-def measured_traffic(w: si.Workload, steps: int, features: bool = False):
-    """HBM bytes per attention launch from the committed rocprofv3 counter summary (FETCH_SIZE and
-    WRITE_SIZE runs of this same command, each scaled on a plain copy of known size); None when the
-    summary does not cover this workload / step count."""
-    if w.name != "cfg1-qwen3-4b-layer" or steps != w.steps or features:
-        return None
-    path = os.path.join(ROOT, "profiles", "attn_kernel_cfg1_hbm_traffic.txt")
-    try:
-        for line in open(path):
-            if line.startswith("traffic_bytes_per_launch"):
-                return float(line.split("=")[1])
-    except OSError:
-        pass
-    return None
-
-
 def profile_value(fname: str, key: str):
     """A `key = number` line of a committed profile summary, or None."""
     try:
@@ -133,40 +103,72 @@ def feat_bytes(w: si.Workload, lens_row: np.ndarray, chunk_pos: int) -> float:
     return float(w.n_kv_heads * lens_row.sum() * w.group * 4 * 2 * planes)
 
 
-def cpu_baseline(w: si.Workload, threads: int, windows: int = 5):
-    """Time the CPU oracle, as it stands, on a bounded sample of the same workload: the full batch at
-    steady state (cache at budget) for `windows` eviction windows, each L decode steps (append +
-    attention) and one eviction event (score + select + compact)."""
+def cpu_baseline(w: si.Workload, threads: int, start_len: int, clock0: int, n_steps: int, budget_s: float = 25.0):
+    """Time the CPU oracle, as it stands, on the window the GPU timed: the full batch with every row holding
+    `start_len` pairs, step clock at `clock0` (an eviction event after every step t with (clock0 + t + 1) % L
+    == 0), `n_steps` decode steps.  If that is more than about `budget_s` seconds of CPU work, the sample is
+    the first whole eviction windows of it (same cache lengths) and the rate is an extrapolation to the whole
+    region.  Seconds are kept per part: append + attention, score, select, compact."""
     import oracle
-    oracle.set_threads(threads)
     B, L, Bt = w.budget, w.interval, w.batch
-    wl = w.scaled(prompt=B)  # steady state: rows already hold B pairs
-    c = oracle.new_cache(w.dtype, Bt, w.n_kv_heads, w.capacity, w.head_dim)
-    K, V = si.gen_kv(wl, 0, 0, B)
-    c.K[:, :, :B], c.V[:, :, :B] = si.storage_array(K, w.dtype), si.storage_array(V, w.dtype)
-    c.pos[:, :, :B] = np.arange(B, dtype=np.int32)
-    c.len[:] = B
+    # about 22 ms per step of the Qwen3-4B layer shape on 16 cores: bound the sample by whole windows
+    per_step = 2.2e-2 * (Bt * w.n_kv_heads * (B + L) * w.head_dim) / (128 * 2176 * 128) * (16.0 / max(threads, 1))
+    max_steps = max(L, int(budget_s / max(per_step, 1e-9)) // L * L)
+    sample = n_steps if n_steps <= max_steps else max_steps
+    wl = w
     W1, b1, W2, b2 = si.gen_scorer(w, 0)
     scorer = (si.storage_array(W1, w.dtype), b1, W2, b2)
-    n_steps = windows * L
-    qs = si.storage_array(si.gen_q(wl, 0, B, B + n_steps), w.dtype)
-    ks, vs = (si.storage_array(x, w.dtype) for x in si.gen_kv(wl, 0, B, B + n_steps))
+    K, V = si.gen_kv(wl, 0, 0, start_len)
+    K, V = si.storage_array(K, w.dtype), si.storage_array(V, w.dtype)
+    qs = si.storage_array(si.gen_q(wl, 0, start_len, start_len + sample), w.dtype)
+    ks, vs = (si.storage_array(x, w.dtype) for x in si.gen_kv(wl, 0, start_len, start_len + sample))
     step_in = [(np.ascontiguousarray(qs[:, :, t]), np.ascontiguousarray(ks[:, :, t]), np.ascontiguousarray(vs[:, :, t]),
-                np.full(Bt, B + t, np.int32)) for t in range(n_steps)]
-    t0 = time.perf_counter()
-    oracle.run_protocol(c, lambda t: step_in[t], n_steps, scorer, B, L, w.softmax_scale, method="sort")
-    dt = time.perf_counter() - t0
-    assert int(c.len[0]) == B
-    # the same loop on ONE core, one window (the cache is back at B after the run above)
-    oracle.set_threads(1)
-    t0 = time.perf_counter()
-    oracle.run_protocol(c, lambda t: step_in[t], L, scorer, B, L, w.softmax_scale, method="sort")
-    dt1 = time.perf_counter() - t0
+                np.full(Bt, start_len + t, np.int32)) for t in range(sample)]
+
+    def run(nthreads):
+        oracle.set_threads(nthreads)
+        c = oracle.new_cache(w.dtype, Bt, w.n_kv_heads, w.capacity, w.head_dim)
+        c.K[:, :, :start_len], c.V[:, :, :start_len] = K, V
+        c.pos[:, :, :start_len] = np.arange(start_len, dtype=np.int32)
+        c.len[:] = start_len
+        part = {"append_attention": 0.0, "score": 0.0, "select": 0.0, "compact": 0.0}
+        events = 0
+        t_all = time.perf_counter()
+        for t in range(sample):
+            q, kn, vn, pn = step_in[t]
+            t0 = time.perf_counter()
+            oracle.append(c, kn, vn, pn)
+            oracle.decode_attn(c, q, w.softmax_scale)
+            t1 = time.perf_counter()
+            part["append_attention"] += t1 - t0
+            if (clock0 + t + 1) % L == 0:
+                sc = oracle.score_kv(c, *scorer)
+                t2 = time.perf_counter()
+                keep = oracle.select_keep(sc.astype(np.float32), c.pos, c.len, B, L, "sort")
+                t3 = time.perf_counter()
+                oracle.compact(c, keep, B)
+                t4 = time.perf_counter()
+                part["score"] += t2 - t1
+                part["select"] += t3 - t2
+                part["compact"] += t4 - t3
+                events += 1
+        return time.perf_counter() - t_all, part, events
+
+    dt, part, events = run(threads)
+    what = (f"full batch ({Bt} sequences x {w.n_kv_heads} KV heads), rows at {start_len} pairs, {sample} decode steps "
+            f"with {events} eviction event(s)")
+    out = {"value": Bt * sample / dt, "unit": "tokens/s", "cores": threads, "kind": "oracle",
+           "sample": f"{what}, {dt:.1f}s CPU on {threads} cores"
+                     + ("" if sample == n_steps else f"; EXTRAPOLATED: the first {sample} of the {n_steps} timed steps, same cache lengths in every window"),
+           "extrapolated": sample != n_steps, "seconds_by_part": {k: round(v, 3) for k, v in part.items()},
+           "events_in_sample": events}
+    if dt * threads * 0.7 <= 40.0:   # the same sample on ONE core, when that stays within the time bound
+        dt1, part1, _ = run(1)
+        out["value_1core"] = Bt * sample / dt1
+        out["sample_1core"] = f"the same sample on one core, {dt1:.1f}s CPU"
+        out["seconds_by_part_1core"] = {k: round(v, 3) for k, v in part1.items()}
     oracle.set_threads(threads)
-    return {"value": Bt * n_steps / dt, "unit": "tokens/s", "cores": threads, "kind": "oracle",
-            "sample": f"full batch ({Bt} sequences x {w.n_kv_heads} KV heads) at steady state (cache {B}..{B + L}): "
-                      f"{windows} windows of {L} decode steps + 1 eviction event each = {n_steps} steps, {dt:.1f}s CPU",
-            "value_1core": Bt * L / dt1, "sample_1core": f"one such window on one core, {dt1:.1f}s CPU"}
+    return out
 
 
 def bench_golden(args):
@@ -369,6 +371,7 @@ def main():
     ap.add_argument("--workload", choices=["decode", "golden"], default="decode",
                     help="decode: the budgeted decode + evict path (the headline); golden: the Golden Eviction label builder")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
+    ap.add_argument("--no-cold", action="store_true", help="skip the HBM-resident (rotating cache copies) attention measurement")
     ap.add_argument("--no-kernel-timing", action="store_true", help="skip the HIP-event pass over the attention launches")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -390,20 +393,38 @@ def main():
         return bench_stack(args, w)
     if w.layers != 1:   # stacks: every layer runs the same kernels on its own cache; without --stack one layer is timed
         w = w.scaled(name=f"{w.name} (one layer of {w.layers})", layers=1)
-    if args.prompt is not None:
-        w = w.scaled(name=f"{w.name} (prompt {args.prompt})", prompt=args.prompt)
     if args.hidden is not None:
         w = w.scaled(name=f"{w.name} (scorer hidden {args.hidden})", hidden=args.hidden)
+    B, L = w.budget, w.interval
     K_steps = args.steps if args.steps is not None else w.steps
     W_steps = args.warmup
+    # Where the run starts.  Default: the steady state of the protocol (Section 3.1: the cache swings between B and
+    # B + L).  Rows start at B + c0 pairs with the step clock at c0, c0 chosen so that the LAST timed step is followed
+    # by an eviction event: any number of steps, also fewer than L, times real events at the cache sizes of a long
+    # generation.  --prompt P: start from a prompt of P tokens at clock 0 instead (the cache first grows to B + L).
+    # Workloads with ragged initial lengths start from those lengths.
+    ragged = len(set(int(x) for x in si.initial_lengths(w))) > 1
+    steady = args.prompt is None and not ragged
+    if steady:
+        clock0 = (L - K_steps % L) % L
+        start_len = B + clock0
+        clock0_w = (L - W_steps % L) % L
+        start_len_w = B + clock0_w
+    else:
+        if args.prompt is not None:
+            w = w.scaled(name=f"{w.name} (prompt {args.prompt})", prompt=args.prompt)
+        clock0 = clock0_w = 0
+        start_len = start_len_w = None
+    lens0 = si.initial_lengths(w) if not steady else np.full(w.batch, start_len, np.int32)
+    lens0_w = lens0 if not steady else np.full_like(lens0, start_len_w)
     n_gen = max(K_steps, W_steps)
-    lens0 = si.initial_lengths(w)
-    B, L = w.budget, w.interval
 
     t0 = time.time()
-    Kh, Vh, posh = gen_prompt(w, lens0, host_threads)
+    # the cache is generated up to the longest start in use, so that the warm-up can start from its own length
+    fill = lens0 if not steady else np.full_like(lens0, max(start_len, start_len_w))
+    Kh, Vh, posh = gen_prompt(w, fill, host_threads)
     qh, kh, vh, ph = gen_step_inputs(w, lens0, n_gen, host_threads)
-    log(f"[bench] generated {w.name}: prompt + {n_gen} steps in {time.time() - t0:.1f}s")
+    log(f"[bench] generated {w.name}: cache + {n_gen} steps in {time.time() - t0:.1f}s")
 
     def dev(a):
         if a.dtype == np.uint16:
@@ -411,8 +432,10 @@ def main():
         return torch.from_numpy(a).cuda()
 
     K0, V0, pos0 = dev(Kh), dev(Vh), dev(posh)
-    len0 = dev(np.repeat(lens0.astype(np.int32)[:, None], w.n_kv_heads, axis=1))      # one count per row
+    rep = lambda l: np.repeat(l.astype(np.int32)[:, None], w.n_kv_heads, axis=1)      # one count per row
+    len0, len0_w = dev(rep(lens0)), dev(rep(lens0_w))
     dq, dk, dv, dp = dev(qh), dev(kh), dev(vh), dev(ph)
+    dp_w = dev((ph - lens0[None, :] + lens0_w[None, :]).astype(np.int32))   # the warm-up counts positions from its own start
     del Kh, Vh, qh, kh, vh
     W1, b1, W2, b2 = si.gen_scorer_feat(w, 0) if args.features else si.gen_scorer(w, 0)
     dW = [dev(si.storage_array(W1, w.dtype)), dev(b1), dev(W2), dev(b2)]
@@ -421,41 +444,63 @@ def main():
     ws = fk.new_attn_workspace(desc)
     feat = fk.new_feat(desc) if args.features else None
     fws = fk.new_feat_workspace(desc) if args.features else None
-    out = torch.empty((w.batch, w.n_q_heads, w.head_dim), dtype=desc.torch_dtype, device="cuda")
+    dout = torch.empty((L, w.batch, w.n_q_heads, w.head_dim), dtype=desc.torch_dtype, device="cuda")  # outputs of one window
     scores = torch.zeros((w.batch, w.n_kv_heads, w.capacity), dtype=torch.float32, device="cuda")
     keep = torch.zeros((w.batch, w.n_kv_heads, B), dtype=torch.int32, device="cuda")
+    slot_idx = torch.arange(B, dtype=torch.int32, device="cuda")
     noise_pool = None
     if args.policy == "sampled":   # Gumbel noise per slot, a pool of 8 independent draws cycled over the events
         noise_pool = [dev(si.gen_gumbel(w.seed, (w.batch, w.n_kv_heads, w.capacity), event=e)) for e in range(8)]
-    lens_at, _ = len_schedule(w, lens0, n_gen)
-    max_at = lens_at.max(axis=1)
     scale = w.softmax_scale
     stream = torch.cuda.current_stream()
 
-    def reset():
-        Kc.copy_(K0); Vc.copy_(V0); posc.copy_(pos0); lenc.copy_(len0)
+    def schedule(l0, c0, n_steps):
+        """Host replay of the protocol's cache sizes: lens [n_steps, Bt] at the attention of step t, and the steps
+        after which an event runs."""
+        lens = l0.astype(np.int64).copy()
+        out = np.empty((n_steps, w.batch), np.int64)
+        ev = []
+        for t in range(n_steps):
+            lens += 1
+            out[t] = lens
+            if (c0 + t + 1) % L == 0:
+                ev.append(t)
+                lens = np.minimum(lens, B)
+        return out, ev
+
+    def reset(l0_dev):
+        Kc.copy_(K0); Vc.copy_(V0); posc.copy_(pos0); lenc.copy_(l0_dev)
         if feat is not None:
             feat.zero_()
 
-    ev_kernels = []
-
-    def run(n_steps, ev_pairs=None):
-        for t in range(n_steps):
-            ml = int(min(max_at[t], w.capacity))
-            if ev_pairs is not None and t % L == 0:
-                ev_pairs[t // L][0].record(stream)
+    def run(n_steps, c0, lens_at, pos_dev, rec=None):
+        """n_steps decode steps from the current device state with the step clock at c0.  Steps between two events go
+        to the library as ONE fk_decode_window call (the host comes back once per window, not once per step).  rec:
+        dict of lists that receives HIP-event pairs around every window's attention launches and around each of the
+        three event kernels, and the number of moved pairs per event."""
+        t = 0
+        while t < n_steps:
+            seg = min(L - (c0 + t) % L, n_steps - t)
+            ml = int(min(lens_at[t].max(), w.capacity))
+            if rec is not None:
+                e = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+                e[0].record(stream)
             if feat is None:
-                fk.fk_decode_step(desc, dq[t], Kc, Vc, posc, lenc, dk[t], dv[t], dp[t], ml, scale, out, ws, stream)
+                fk.fk_decode_window(desc, dq[t:t + seg], Kc, Vc, posc, lenc, dk[t:t + seg], dv[t:t + seg], pos_dev[t:t + seg], seg, ml,
+                                    scale, dout[:seg], ws, stream)
             else:
-                fk.fk_decode_step_feat(desc, dq[t], Kc, Vc, posc, lenc, dk[t], dv[t], dp[t], ml, scale, feat, t % L, L, out,
-                                       fws, stream)
-            if ev_pairs is not None and ((t + 1) % L == 0 or t + 1 == n_steps):
-                ev_pairs[t // L][1].record(stream)
-            if (t + 1) % L == 0:
+                for u in range(t, t + seg):
+                    fk.fk_decode_step_feat(desc, dq[u], Kc, Vc, posc, lenc, dk[u], dv[u], pos_dev[u], int(min(lens_at[u].max(), w.capacity)),
+                                           scale, feat, (c0 + u) % L, L, dout[u - t], fws, stream)
+            if rec is not None:
+                e[1].record(stream)
+                rec["attn"].append((t, seg, e))
+            t += seg
+            if (c0 + t) % L == 0:
+                ml = int(min(lens_at[t - 1].max(), w.capacity))
                 kev = None
-                if ev_pairs is not None:   # per-kernel brackets of the event: [start, after score, after select, after compact]
+                if rec is not None:   # [start, after score, after select, after compact]
                     kev = [torch.cuda.Event(enable_timing=True) for _ in range(4)]
-                    ev_kernels.append((t, kev))
                     kev[0].record(stream)
                 if feat is None:
                     fk.fk_score_kv(desc, Kc, Vc, lenc, ml, *dW, scores, stream, skip_len=B)
@@ -466,7 +511,7 @@ def main():
                 if noise_pool is None:
                     fk.fk_select_keep(desc, scores, posc, lenc, ml, B, L, keep, stream)
                 else:
-                    fk.fk_select_keep_sampled(desc, scores, noise_pool[(t // L) % 8], posc, lenc, ml, B, L, 2 * L, keep, stream)
+                    fk.fk_select_keep_sampled(desc, scores, noise_pool[((c0 + t) // L) % 8], posc, lenc, ml, B, L, 2 * L, keep, stream)
                 if kev:
                     kev[2].record(stream)
                 if feat is None:
@@ -475,94 +520,145 @@ def main():
                     fk.fk_compact_feat(desc, Kc, Vc, posc, feat, lenc, keep, B, stream)
                 if kev:
                     kev[3].record(stream)
+                    rec["events"].append((t - 1, kev))
+                    # pairs whose slot changes (the kept ones already in place cost the compaction nothing)
+                    rec["moved"].append((keep != slot_idx).sum() if (lens_at[t - 1] > B).all() else None)
 
-    # warm-up (untimed), then restart from the prompt
-    reset()
-    run(W_steps)
+    lens_at_w, _ = schedule(lens0_w, clock0_w, W_steps) if W_steps else (None, [])
+    lens_at, ev_steps = schedule(lens0, clock0, K_steps)
+    # warm-up (untimed; with the default start it ends with a full eviction event), then set the timed start state
+    if W_steps:
+        reset(len0_w)
+        run(W_steps, clock0_w, lens_at_w, dp_w)
     torch.cuda.synchronize()
-    reset()
+    reset(len0)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    run(K_steps)
+    run(K_steps, clock0, lens_at, dp)
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
     final_len = lenc.cpu().numpy()
     assert (final_len == final_len[:, :1]).all()
     final_len = final_len[:, 0]
-    expect_len = len_schedule(w, lens0, K_steps)[0][-1]
-    expect_len = np.where((K_steps % L == 0) & (expect_len > B), B, expect_len)
+    expect_len = lens_at[-1].copy()
+    if ev_steps and ev_steps[-1] == K_steps - 1:
+        expect_len = np.minimum(expect_len, B)
     assert np.array_equal(final_len, expect_len), (final_len, expect_len)
 
     tokens_per_s = w.batch * K_steps / wall
     total_attn_bytes = sum(attn_bytes(w, lens_at[t]) for t in range(K_steps))
     if args.features:
-        total_attn_bytes += sum(feat_bytes(w, lens_at[t], t % L) for t in range(K_steps))
+        total_attn_bytes += sum(feat_bytes(w, lens_at[t], (clock0 + t) % L) for t in range(K_steps))
+    ws_mb = 2 * w.batch * w.n_kv_heads * float(lens_at.mean()) * w.head_dim * w.elem_bytes / 1e6
+    n_events = len(ev_steps)
+    parts = "attention + scorer + top-k + compaction" if n_events else "attention only: no eviction event falls into the timed steps"
     result = {
-        "metric": "decode tokens/s, budgeted KV decode+evict (attention + scorer + top-k + compaction), one layer",
+        "metric": f"decode tokens/s, budgeted KV decode+evict ({parts}), one layer",
         "value": tokens_per_s, "unit": "tokens/s", "n_gpus": 1, "steps": K_steps, "warmup": W_steps,
         "ms_per_step": 1e3 * wall / K_steps, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": w.dtype, "data": "synthetic",
         "config": {"workload": w.name, "batch": w.batch, "n_q_heads": w.n_q_heads, "n_kv_heads": w.n_kv_heads,
-                   "head_dim": w.head_dim, "prompt": w.prompt, "budget": B, "eviction_interval": L,
+                   "head_dim": w.head_dim, "budget": B, "eviction_interval": L,
                    "capacity": w.capacity, "scorer_hidden": w.hidden, "eviction_policy": args.policy,
-                   "scorer_inputs": "k, v, attention features" if args.features else "k, v"},
+                   "scorer_inputs": "k, v, attention features" if args.features else "k, v",
+                   "start": ("steady state of the protocol: rows pre-filled to start_len, step clock offset so that the last timed step is followed by an eviction event"
+                             if steady else "prompt, step clock 0"),
+                   "start_len": int(lens0.max()) if steady else [int(lens0.min()), int(lens0.max())],
+                   "cache_len_range_timed": [int(lens_at.min()), int(lens_at.max())],
+                   "events_in_timed_region": n_events, "events_in_warmup": len(schedule(lens0_w, clock0_w, W_steps)[1]) if W_steps else 0},
         "path_gbs_algorithmic": total_attn_bytes / wall / 1e9,
     }
-    # the same with the eviction events' algorithmic bytes added (rows over budget at the event: every retained
-    # pair scored, its score read by the selection, the kept slots written, every kept pair that is not already in
-    # place moved; "every kept pair" is taken, an upper bound)
-    ev_bytes = 0.0
-    for t in range(L - 1, K_steps, L):
-        over = lens_at[t] > B
-        pairs = float(lens_at[t][over].sum()) * w.n_kv_heads
-        rows_over = float(over.sum()) * w.n_kv_heads
-        ev_bytes += pairs * (2 * w.head_dim * w.elem_bytes + 4) + 4 * pairs + rows_over * 4 * B \
-            + rows_over * B * (4 * w.head_dim * w.elem_bytes + 8)
-    result["path_with_events"] = {"gbs_algorithmic": (total_attn_bytes + ev_bytes) / wall / 1e9,
-                                  "frac_of_hbm_peak": (total_attn_bytes + ev_bytes) / wall / 1e9 / HBM_PEAK_GBS,
-                                  "event_bytes_share": ev_bytes / (total_attn_bytes + ev_bytes)}
 
     if not args.no_kernel_timing:
-        # second pass over the same steps with HIP events (on the launch stream) bracketing the attention
-        # launches of every eviction window: first launch of the window .. last launch before the event
-        # kernels.  elapsed / launches is the average launch duration, inter-launch gaps included.
-        reset()
-        n_win = (K_steps + L - 1) // L
-        pairs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n_win)]
-        run(K_steps, pairs)
+        # second pass over the same steps with HIP events (on the launch stream) around every window's attention
+        # launches and around each kernel of every event
+        reset(len0)
+        rec = {"attn": [], "events": [], "moved": []}
+        run(K_steps, clock0, lens_at, dp, rec)
         torch.cuda.synchronize()
-        total_ms = sum(a.elapsed_time(b) for a, b in pairs)
-        ms = np.array([total_ms / K_steps])
+        attn_ms = sum(e[0].elapsed_time(e[1]) for _, _, e in rec["attn"])
+        attn_us = attn_ms * 1e3 / K_steps
         avg_bytes = total_attn_bytes / K_steps
-        achieved = avg_bytes / (ms.mean() * 1e-3) / 1e9
-        result["roofline"] = {"kernel": "attn_kernel (fk_decode_step_feat: append + attention + attention-feature update, one launch)" if args.features
-                              else "attn_kernel (fk_decode_step: append + split-K attention + merge, one launch)", "bound": "hbm", "achieved": achieved,
-                              "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
-                              "traffic": measured_traffic(w, K_steps, args.features),
-                              "avg_launch_us": float(ms.mean() * 1e3), "algorithmic_bytes_per_launch": avg_bytes}
-        # the event kernels, over the events in which every row is over budget (HIP events between the calls)
-        full = [(t, kev) for (t, kev) in ev_kernels if lens_at[t].min() > B]
+        achieved = avg_bytes / (attn_us * 1e-6) / 1e9
+        ratio = profile_value("attn_kernel_cfg1_hbm_traffic.txt", "traffic_over_algorithmic") \
+            if (w.name.startswith("cfg1-qwen3-4b-layer") and steady and not args.features and args.hidden is None) else None
+        result["roofline"] = {
+            "kernel": "attn_kernel (fk_decode_step_feat: append + attention + attention-feature update, one launch)" if args.features
+            else "attn_kernel (fk_decode_step via fk_decode_window: append + attention, one launch per step)",
+            "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
+            "traffic": None if ratio is None else ratio * avg_bytes,
+            "traffic_source": None if ratio is None else "profiles/attn_kernel_cfg1_hbm_traffic.txt: counter bytes / algorithmic bytes at the same steady state, times this run's algorithmic bytes",
+            "avg_launch_us": attn_us, "algorithmic_bytes_per_launch": avg_bytes,
+            "working_set_mb": ws_mb,
+            "resident_in": "infinity cache (the K + V of this one layer are re-read every step and fit its 256 MB)" if ws_mb < 256 else "hbm"}
+        # the event kernels over the events in which every row is over budget
+        full = [(t, kev) for (t, kev) in rec["events"] if lens_at[t].min() > B]
         if full:
             us = [float(np.mean([k[i].elapsed_time(k[i + 1]) for _, k in full])) * 1e3 for i in range(3)]
             pairs = float(np.mean([lens_at[t].sum() for t, _ in full])) * w.n_kv_heads   # retained pairs scored per event
+            moved = [float(m.item()) for m in rec["moved"] if m is not None]
+            moved = float(np.mean(moved)) if moved else 0.0
             rows_ = w.batch * w.n_kv_heads
             e = w.elem_bytes
             sc_bytes = pairs * (2 * w.head_dim * e + 4)
             sc_flops = pairs * (2.0 * (2 * w.head_dim + (6 * w.group if args.features else 0)) * w.hidden + 4 * w.hidden)
             sel_bytes = 4 * pairs + rows_ * 4 * B
-            cp_bytes = rows_ * B * (2 * 2 * w.head_dim * e + 8)
+            cp_bytes = moved * (2 * 2 * w.head_dim * e + 8)      # read + write of K, V rows and the position of every moved pair
+            ev_us = sum(us)
             result["event_kernels"] = {
-                "events_timed": len(full), "pairs_per_event": pairs,
-                "score": {"us": us[0], "algorithmic_gbs": sc_bytes / us[0] / 1e3, "tflops": sc_flops / us[0] / 1e6},
+                "events_timed": len(full), "pairs_per_event": pairs, "moved_pairs_per_event": moved, "event_us": ev_us,
+                "score": {"us": us[0], "algorithmic_gbs": sc_bytes / us[0] / 1e3, "tflops": sc_flops / us[0] / 1e6,
+                          "frac_of_hbm_peak": sc_bytes / us[0] / 1e3 / HBM_PEAK_GBS, "frac_of_bf16_mfma_peak": sc_flops / us[0] / 1e6 / 2500.0},
                 "select": {"us": us[1], "algorithmic_gbs": sel_bytes / us[1] / 1e3},
-                "compact": {"us": us[2], "algorithmic_gbs_upper": cp_bytes / us[2] / 1e3,
-                            "note": "bytes if every kept pair moved; includes the length clamp launch"}}
+                "compact": {"us": us[2], "algorithmic_gbs": cp_bytes / us[2] / 1e3}}
+            ev_bytes = len(full) * (sc_bytes + sel_bytes + cp_bytes)
+            result["path_with_events"] = {"gbs_algorithmic": (total_attn_bytes + ev_bytes) / wall / 1e9,
+                                          "frac_of_hbm_peak": (total_attn_bytes + ev_bytes) / wall / 1e9 / HBM_PEAK_GBS,
+                                          "event_bytes_share": ev_bytes / (total_attn_bytes + ev_bytes)}
+            # what a long generation pays per step: one attention launch plus 1/L of an event
+            result["amortised"] = {"tokens_per_s": w.batch / ((attn_us + ev_us / L) * 1e-6), "us_per_step": attn_us + ev_us / L,
+                                   "note": "AMORTISED over a whole eviction window from the HIP-event component times: attention launch + event / L; "
+                                           "`value` is the wall clock of the timed steps as they ran"}
+        result["host_gap_us_per_step"] = 1e3 * wall / K_steps - (attn_us + (sum(k[0].elapsed_time(k[3]) for _, k in rec["events"]) * 1e3 / K_steps))
+
+        if w.dtype == "bf16" and w.head_dim == 128 and not args.features and not args.no_cold:
+            # The same launches with the cache coming from HBM: the attention of a deep stack visits another layer's
+            # cache at every launch.  Here: copies of this layer's cache, enough of them to exceed the Infinity Cache
+            # several times, visited in turn with the cold-cache flag set; len is restored between rounds.
+            n_copies = max(4, int(np.ceil(1536.0 / ws_mb)))
+            cdesc = fk.CacheDesc(w.batch, w.n_q_heads, w.n_kv_heads, w.head_dim, w.capacity, w.dtype, cold=True)
+            cws = fk.new_attn_workspace(cdesc)
+            reset(len0)
+            copies = [(Kc.clone(), Vc.clone(), posc.clone(), lenc.clone()) for _ in range(n_copies)]
+            n_round = min(16, w.capacity - int(lens0.max()) - 1)
+            ml = int(min(lens0.max() + n_round + 1, w.capacity))
+            def cold_pass():
+                for r in range(n_round):
+                    for (Kx, Vx, px, lx) in copies:
+                        fk.fk_decode_step(cdesc, dq[r], Kx, Vx, px, lx, dk[r], dv[r], dp[r], ml, scale, dout[0], cws, stream)
+            cold_pass()
+            for c_ in copies:
+                c_[3].copy_(len0)
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(stream)
+            cold_pass()
+            e1.record(stream)
+            torch.cuda.synchronize()
+            c_us = e0.elapsed_time(e1) * 1e3 / (n_round * n_copies)
+            c_bytes = float(np.mean([attn_bytes(w, lens0 + r + 1) for r in range(n_round)]))
+            result["roofline_hbm_resident"] = {
+                "kernel": "attn_kernel (fk_decode_step with FK_CACHE_COLD), one launch per cache copy in turn", "bound": "hbm",
+                "achieved": c_bytes / c_us / 1e3, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": c_bytes / c_us / 1e3 / HBM_PEAK_GBS,
+                "avg_launch_us": c_us, "algorithmic_bytes_per_launch": c_bytes, "cache_copies": n_copies,
+                "working_set_mb": ws_mb * n_copies, "resident_in": "hbm"}
+            del copies
     if "roofline" in result:
         # achievable streaming-read bandwidth on this machine, beside the nominal peak: the K cache of this
         # workload (fits the Infinity Cache at the default shape) and a 4 GiB buffer (HBM resident)
         sink = torch.zeros(4, dtype=torch.int32, device="cuda")
         big = torch.empty(1 << 30, dtype=torch.int32, device="cuda")
-        big.fill_(1)
+        big.random_(0, 1 << 30)
         def stream_gbs(t, iters):
             for _ in range(3):
                 fk.fk_stream_read(t, sink, stream)
@@ -575,8 +671,8 @@ def main():
             return t.numel() * t.element_size() * iters / (e0.elapsed_time(e1) * 1e-3) / 1e9
         result["roofline"]["stream_read_gbs"] = {"k_cache": stream_gbs(Kc, 50), "buffer_4gib": stream_gbs(big, 10)}
         del big
-    if not args.no_cpu and not args.features:   # the oracle's protocol loop covers the default path
-        result["cpu_baseline"] = cpu_baseline(w, host_threads)
+    if not args.no_cpu and not args.features and steady:   # the oracle's protocol loop covers the default path
+        result["cpu_baseline"] = cpu_baseline(w, host_threads, int(lens0.max()), clock0, K_steps)
     print(json.dumps(result), flush=True)
 
 

@@ -126,6 +126,20 @@ fk_status fk_decode_step(const fk_cache_desc *desc, const void *q, void *K, void
                          size_t workspace_bytes, void *stream);
 
 /*
+ * Section 3.1 (the L generation steps between two eviction events): n_steps consecutive fk_decode_step calls
+ * enqueued by one call, step t on q_seq[t], k_seq[t], v_seq[t], pos_seq[t] with its output in out_seq[t] and
+ * max_len = min(max_len_first + t, capacity); max_len_first bounds len[r] + 1 at the first step.
+ *   q_seq, out_seq [n_steps][batch][n_q_heads][head_dim], k_seq, v_seq [n_steps][batch][n_kv_heads][head_dim]
+ *   dtype; pos_seq [n_steps][batch] int32.
+ * Results are those of the n_steps single calls; the host returns to its caller once per window instead
+ * of once per step.  n_steps == 0 is a no-op.  On an error the steps before it stay enqueued.
+ */
+fk_status fk_decode_window(const fk_cache_desc *desc, const void *q_seq, void *K, void *V, int32_t *pos,
+                           int32_t *len, const void *k_seq, const void *v_seq, const int32_t *pos_seq,
+                           int32_t n_steps, int32_t max_len_first, float softmax_scale, void *out_seq,
+                           void *workspace, size_t workspace_bytes, void *stream);
+
+/*
  * Section 3.1 Eq. 1 and Appendix B.1 (importance score of every retained pair, features
  * restricted to the key and value vectors):
  *   scores[b][h][i] = sum_j gelu(sum_f x_f W1[f][j] + b1[j]) W2[j] + b2,  x = [K[b][h][i], V[b][h][i]]
@@ -260,13 +274,6 @@ fk_status fk_golden_scores(const void *A, int32_t dtype, int32_t n_q_heads, int3
  */
 fk_status fk_golden_trace(const float *alpha, int32_t n_kv_heads, int32_t T, int32_t budget,
                           int32_t interval, int32_t *kept, void *stream);
-
-/*
- * Measurement helper, not part of the method: reads `bytes` (>= 16) of device memory at `src` with
- * 16-byte loads (non-temporal from 352 MB on, like the attention kernel) and discards them; `sink` is 4 bytes of device memory.  bench.py times it to report
- * the achievable streaming bandwidth of the box beside the nominal HBM peak.
- */
-fk_status fk_stream_read(const void *src, size_t bytes, void *sink, void *stream);
 
 #ifdef __cplusplus
 }

@@ -15,44 +15,60 @@ extern "C" const char* fk_status_string(fk_status s) {
 extern "C" const char* fk_version(void) { return "fk 0.1 gfx950"; }
 
 // ---------------------------------------------------------------------------------------
-// measurement helper: plain streaming read (16 bytes per lane, grid-stride), the achievable
-// bandwidth that bench.py reports beside the nominal HBM peak
+// measurement helper (declared in fk_bench.h, not part of the method): plain streaming reads, the achievable
+// bandwidth that bench.py reports beside the nominal HBM peak.  Two shapes, each the fastest of a sweep of
+// grid sizes, loads in flight and load kinds on this chip:
+//   beyond the Infinity Cache: every wavefront reads whole 8 KB chunks (8 x 64 lanes x 16 B in flight),
+//     chunks dealt round robin over 512 workgroups of 16 wavefronts, non-temporal loads;
+//   cache-resident sizes: grid-stride over 8192 workgroups of 256 threads, 8 loads in flight.
 // ---------------------------------------------------------------------------------------
+#include "fk_bench.h"
 namespace fk {
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
-template <bool NT>
 __device__ __forceinline__ uint32_t fold16(const uint4* p) {
-    if constexpr (NT) {
-        const u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p));
-        return v.x ^ v.y ^ v.z ^ v.w;
-    } else {
-        const uint4 v = *p;
-        return v.x ^ v.y ^ v.z ^ v.w;
-    }
+    const u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p));
+    return v.x ^ v.y ^ v.z ^ v.w;
 }
-// NT: non-temporal loads, the faster kind for buffers beyond the Infinity Cache (as in the attention kernel)
-template <bool NT>
-__global__ __launch_bounds__(256) void stream_read_kernel(const uint4* __restrict__ p, size_t n16, uint32_t* __restrict__ sink) {
+static constexpr int kStreamU = 8;
+__global__ __launch_bounds__(1024) void stream_read_chunk_kernel(const uint4* __restrict__ p, size_t n16, uint32_t* __restrict__ sink) {
+    const size_t wave = ((size_t)blockIdx.x * blockDim.x + threadIdx.x) / kWave, nwaves = (size_t)gridDim.x * blockDim.x / kWave;
+    const int lane = threadIdx.x & (kWave - 1);
+    constexpr size_t chunk = (size_t)kStreamU * kWave;
+    uint32_t acc = 0;
+    size_t c = wave * chunk;
+    for (; c + chunk <= n16; c += nwaves * chunk) {
+        uint32_t v[kStreamU];
+#pragma unroll
+        for (int u = 0; u < kStreamU; ++u) v[u] = fold16(p + c + u * kWave + lane);
+#pragma unroll
+        for (int u = 0; u < kStreamU; ++u) acc += v[u];
+    }
+    for (size_t i = c + lane; i < n16 && c < n16; i += kWave) acc += fold16(p + i);  // the one ragged chunk
+    if (acc == 0x9e3779b9u) sink[0] = acc;  // keeps the loads alive; practically never true
+}
+__global__ __launch_bounds__(256) void stream_read_stride_kernel(const uint4* __restrict__ p, size_t n16, uint32_t* __restrict__ sink) {
     size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
     const size_t stride = (size_t)gridDim.x * blockDim.x;
     uint32_t acc = 0;
-    for (; i + 3 * stride < n16; i += 4 * stride) {
-        const uint32_t a = fold16<NT>(p + i), b = fold16<NT>(p + i + stride), c = fold16<NT>(p + i + 2 * stride),
-                       d = fold16<NT>(p + i + 3 * stride);
-        acc += a ^ b ^ c ^ d;
+    for (; i + (kStreamU - 1) * stride < n16; i += kStreamU * stride) {
+        uint32_t v[kStreamU];
+#pragma unroll
+        for (int u = 0; u < kStreamU; ++u) v[u] = fold16(p + i + u * stride);
+#pragma unroll
+        for (int u = 0; u < kStreamU; ++u) acc += v[u];
     }
-    for (; i < n16; i += stride) acc += fold16<NT>(p + i);
-    if (acc == 0x9e3779b9u) sink[0] = acc;  // keeps the loads alive; practically never true
+    for (; i < n16; i += stride) acc += fold16(p + i);
+    if (acc == 0x9e3779b9u) sink[0] = acc;
 }
 }  // namespace fk
 
 extern "C" fk_status fk_stream_read(const void* src, size_t bytes, void* sink, void* stream) {
     if (!src || !sink || bytes < 16 || !fk::aligned16(src)) return FK_ERR_INVALID_ARG;
     if (bytes >= ((size_t)352 << 20))
-        hipLaunchKernelGGL(fk::stream_read_kernel<true>, dim3(4096), dim3(256), 0, (hipStream_t)stream, (const uint4*)src,
+        hipLaunchKernelGGL(fk::stream_read_chunk_kernel, dim3(512), dim3(1024), 0, (hipStream_t)stream, (const uint4*)src,
                            bytes / 16, (uint32_t*)sink);
     else
-        hipLaunchKernelGGL(fk::stream_read_kernel<false>, dim3(4096), dim3(256), 0, (hipStream_t)stream, (const uint4*)src,
+        hipLaunchKernelGGL(fk::stream_read_stride_kernel, dim3(8192), dim3(256), 0, (hipStream_t)stream, (const uint4*)src,
                            bytes / 16, (uint32_t*)sink);
     return fk::launch_status();
 }

@@ -98,12 +98,18 @@ template <typename T, int D, int G> struct AttnCfg {
     static constexpr int NG = PVM ? WAVES : WAVES * KG;     // partial accumulators per workgroup
     static constexpr int PS = KT + 8;                       // PVM: bf16 row stride of the P tile in LDS
     static constexpr int KRS = 272;                         // PVM: padded byte stride of a K row in LDS
-    // dynamic LDS: acc [NG][G][D] | m [NG][G] | l [NG][G] | w [NG][G] | M [8] | p [WAVES][KT][GP] | corr [WAVES][GP]
-    //              | PVM only: K tiles [WAVES][KT][KRS] bytes (the fp32 p area holds the bf16 P tile)
+    // dynamic LDS (floats unless noted):
+    //   PVM:   m [NG][G] | l [NG][G] | w [NG][G] | M [8] | P tiles [WAVES][GP][PS] bf16 | K tiles [WAVES][KT][KRS] bytes
+    //          (a wavefront's partial accumulator [G][D] reuses its own K tile once its loop is over), 73 KB at G = 4:
+    //          two workgroups fit the 160 KB of a CU
+    //   other: acc [NG][G][D] | m [NG][G] | l [NG][G] | w [NG][G] | M [8] | p [WAVES][KT][GP] | corr [WAVES][GP]
+    static constexpr int ACC_STRIDE = PVM ? KT * KRS / 4 : G * D;  // floats between the partial accumulators
+    static constexpr size_t HEAD_FLOATS = 3 * (size_t)NG * G + 8;   // m, l, w, M
+    static constexpr size_t PB_BYTES = (size_t)WAVES * GP * PS * 2;  // PVM: the bf16 P tiles
     static constexpr size_t LDS_BYTES =
-        sizeof(float) * ((size_t)NG * G * D + 3 * (size_t)NG * G + 8 + (size_t)WAVES * KT * GP + (size_t)WAVES * GP + 4) +
-        (PVM ? (size_t)WAVES * KT * KRS : 0);
-    // attention-feature variant (PVM only): lx [NG][G] exact normaliser partials | invL [8], behind the K tiles
+        PVM ? sizeof(float) * HEAD_FLOATS + PB_BYTES + (size_t)WAVES * KT * KRS
+            : sizeof(float) * ((size_t)NG * G * D + HEAD_FLOATS + (size_t)WAVES * KT * GP + (size_t)WAVES * GP + 4);
+    // attention-feature variant: lx [NG][G] exact normaliser partials | invL [8], behind everything else
     static constexpr size_t LDS_BYTES_FEAT = LDS_BYTES + sizeof(float) * ((size_t)NG * G + 8);
     static constexpr size_t LX_OFFSET = LDS_BYTES / sizeof(float);  // float index of lx in the dynamic LDS
 };
@@ -111,15 +117,17 @@ template <typename T, int D, int G> struct AttnCfg {
 struct AttnPlan {
     int split_len;  // keys per split (multiple of the wave tile)
     int nsplit;     // splits per row
+    bool rotate;    // workgroups start at different tiles of their splits
 };
 
-// Upper bound on the splits per row.  The bf16 D = 128 kernel saturates HBM from 128 workgroups of
-// eight wavefronts, so rows are split only when there are fewer rows than that (no split = no
-// cross-workgroup merge at the end of the launch); the other kernels want about two per CU.
-static int attn_max_splits(const fk_cache_desc* d) {
+// Splits per row the plan aims at.  The bf16 D = 128 kernel saturates the memory system from 128 workgroups of
+// eight wavefronts when the cache sits in the Infinity Cache, so rows are split only when there are fewer rows
+// than that (no split = no cross-workgroup merge at the end of the launch); a cold cache comes from HBM, whose
+// latency takes every CU to cover: up to 256 workgroups; the other kernels want about two per CU.
+static int attn_want_splits(const fk_cache_desc* d) {
     const int rows = d->batch * d->n_kv_heads;
     if (d->dtype == FK_BF16 && d->head_dim == 128 && (d->flags & FK_CACHE_COLD)) {
-        const int want = 256 / rows;  // a cold cache comes from HBM, whose latency takes every CU to cover: up to 256 workgroups
+        const int want = 256 / rows;
         return want < 1 ? 1 : want;
     }
     const int target = (d->dtype == FK_BF16 && d->head_dim == 128) ? 128 : 512;
@@ -127,18 +135,28 @@ static int attn_max_splits(const fk_cache_desc* d) {
     return want < 1 ? 1 : want;
 }
 
+// Upper bound on the splits any max_len can get (sizes the workspace).
+static int attn_max_splits(const fk_cache_desc* d) { return attn_want_splits(d); }
+
 static AttnPlan attn_plan(const fk_cache_desc* d, int max_len) {
     const int tile = 32;
-    int want = attn_max_splits(d);
+    int want = attn_want_splits(d);
     const int max_split = (max_len + tile - 1) / tile;
     if (want > max_split) want = max_split;
     if (want < 1) want = 1;
     int split_len = (max_len + want - 1) / want;
     split_len = (split_len + tile - 1) / tile * tile;
+    // (Rounding the splits down to whole rounds of the workgroup, with the rest of the row as a short split of its
+    // own, was measured and dropped: more workgroups than CUs end up two to a CU while other CUs idle, 85 -> 112 us
+    // at 64 rows of 16448 keys.)
     AttnPlan p;
     p.split_len = split_len;
     p.nsplit = (max_len + split_len - 1) / split_len;
     if (p.nsplit < 1) p.nsplit = 1;
+    // Start every workgroup at another tile of its split when the splits are long and the cache comes from HBM:
+    // workgroups that walk rows a near power of two apart in step crowd the same memory channels (measured on
+    // 512 MB per launch, 4128 keys per split: 5.2 TB/s in step, 6.3 TB/s rotated); short splits lose 2 % to it.
+    p.rotate = p.nsplit > 1 && split_len >= 2048;
     return p;
 }
 
@@ -159,6 +177,7 @@ struct AttnParams {
     const int32_t* pos_new;
     float scale_log2e;
     int n_kv, cap, split_len, nsplit;
+    int rotate;          // bf16 D = 128: workgroups start at different tiles of their splits
     float* rec;          // [rows][nsplit][G][D + 2]
     uint32_t* row_cnt;   // [rows], zero between launches
     void* out;
@@ -190,13 +209,15 @@ __global__ __launch_bounds__((AttnCfg<T, D, G>::THREADS)) void attn_kernel(const
     const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
 
     extern __shared__ __attribute__((aligned(16))) float smem[];
-    float* s_acc = smem;                      // [NG][G][D]
-    float* s_m = s_acc + (size_t)NG * G * D;   // [NG][G]
+    // PVM: head | P tiles | K tiles, the partial accumulators live in the K tiles; other paths: acc | head | p | corr
+    float* s_m = C::PVM ? smem : smem + (size_t)NG * G * D;  // [NG][G]
     float* s_l = s_m + NG * G;                 // [NG][G]
     float* s_w = s_l + NG * G;                 // [NG][G] merge weights 2^(m_g - M)
     float* s_M = s_w + NG * G;                 // [8] merged maximum per head
-    float* s_p = s_M + 8;                      // [WAVES][KT][GP]
-    float* s_corr = s_p + WAVES * KT * GP;     // [WAVES][GP]
+    float* s_p = s_M + 8;                      // other paths: [WAVES][KT][GP]; PVM: the bf16 P tiles
+    float* s_corr = s_p + WAVES * KT * GP;     // other paths: [WAVES][GP]
+    unsigned char* s_kt = reinterpret_cast<unsigned char*>(s_p) + C::PB_BYTES;  // PVM: K tiles [WAVES][KT][KRS]
+    float* s_acc = C::PVM ? reinterpret_cast<float*>(s_kt) : smem;  // partial g2 at s_acc + g2 * ACC_STRIDE, [G][D]
     __shared__ int s_last;
 
     const bool appending = P.k_new != nullptr;
@@ -314,7 +335,7 @@ __global__ __launch_bounds__((AttnCfg<T, D, G>::THREADS)) void attn_kernel(const
         constexpr int PS = C::PS, KRS = C::KRS;
         const int n16 = lane & 15, quad = lane >> 4;
         uint16_t* my_pb = reinterpret_cast<uint16_t*>(s_p) + (size_t)wave * GP * PS;           // [GP][PS] bf16
-        unsigned char* my_k = reinterpret_cast<unsigned char*>(s_corr + WAVES * GP + 4) + (size_t)wave * KT * KRS;
+        unsigned char* my_k = s_kt + (size_t)wave * KT * KRS;
         B128 qa[4];
 #pragma unroll
         for (int ks = 0; ks < 4; ++ks) {
@@ -333,7 +354,13 @@ __global__ __launch_bounds__((AttnCfg<T, D, G>::THREADS)) void attn_kernel(const
 #pragma unroll
         for (int e = 0; e < 8; ++e) o[e] = (f32x4_t){0.f, 0.f, 0.f, 0.f};
 
-        for (int base = start + wave * KT; base < end; base += WAVES * KT) {
+        // Tiles are dealt round robin to the wavefronts; with P.rotate the deal starts from a tile that differs
+        // from workgroup to workgroup (the online softmax does not care about the order).
+        const int ntiles = (end - start + KT - 1) / KT;
+        const int rot = P.rotate ? (int)(((unsigned)row * 37u + (unsigned)split * 11u) % (unsigned)ntiles) : 0;
+        for (int t = wave; t < ntiles; t += WAVES) {
+            const int tt = t + rot < ntiles ? t + rot : t + rot - ntiles;
+            const int base = start + tt * KT;
             uint4 vr[8];
             {
                 uint4 kr[8];  // lane (quad, n16): key base + quad*8 + u, 16-byte chunk n16
@@ -429,7 +456,7 @@ __global__ __launch_bounds__((AttnCfg<T, D, G>::THREADS)) void attn_kernel(const
             const int h = quad * 4 + i;
             const float ls = group_sum<16>(l_run[i]);
             if (h < G) {
-                float* dst = s_acc + ((size_t)wave * G + h) * D + n16 * 8;
+                float* dst = s_acc + (size_t)wave * C::ACC_STRIDE + (size_t)h * D + n16 * 8;  // own K tile: its loop is over
                 *reinterpret_cast<float4*>(dst) = make_float4(o[0][i], o[1][i], o[2][i], o[3][i]);
                 *reinterpret_cast<float4*>(dst + 4) = make_float4(o[4][i], o[5][i], o[6][i], o[7][i]);
                 if (n16 == 0) {
@@ -646,7 +673,7 @@ __global__ __launch_bounds__((AttnCfg<T, D, G>::THREADS)) void attn_kernel(const
 
     // ---- merge the partials of the workgroup -----------------------------------------------------
     if constexpr (!C::PVM) {
-        float* dst = s_acc + ((size_t)(wave * KG + kgv) * G) * D + dl * EPL;
+        float* dst = s_acc + (size_t)(wave * KG + kgv) * C::ACC_STRIDE + dl * EPL;
 #pragma unroll
         for (int h = 0; h < G; ++h)
 #pragma unroll
@@ -670,7 +697,7 @@ __global__ __launch_bounds__((AttnCfg<T, D, G>::THREADS)) void attn_kernel(const
         const float mn = s_M[h];
         float a = 0.f, ls = 0.f;
 #pragma unroll 8
-        for (int g2 = 0; g2 < NG; ++g2) a = fmaf(s_acc[((size_t)g2 * G + h) * D + d], s_w[g2 * G + h], a);
+        for (int g2 = 0; g2 < NG; ++g2) a = fmaf(s_acc[(size_t)g2 * C::ACC_STRIDE + (size_t)h * D + d], s_w[g2 * G + h], a);
         if (d == 0 || used == 1) {
 #pragma unroll 8
             for (int g2 = 0; g2 < NG; ++g2) ls = fmaf(s_l[g2 * G + h], s_w[g2 * G + h], ls);
@@ -786,6 +813,7 @@ static fk_status attn_launch(const fk_cache_desc* d, const AttnParams& base, int
     AttnParams P = base;
     P.split_len = p.split_len;
     P.nsplit = p.nsplit;
+    P.rotate = p.rotate ? 1 : 0;
     P.row_cnt = reinterpret_cast<uint32_t*>(ws);
     P.rec = reinterpret_cast<float*>(reinterpret_cast<char*>(ws) + attn_counter_bytes(d));
     if constexpr (C::PVM) {
@@ -890,6 +918,28 @@ extern "C" fk_status fk_decode_step(const fk_cache_desc* desc, const void* q, vo
     P.pos_new = pos_new;
     P.out = out;
     return attn_entry(desc, P, max_len, softmax_scale, workspace, workspace_bytes, stream);
+}
+
+extern "C" fk_status fk_decode_window(const fk_cache_desc* desc, const void* q_seq, void* K, void* V, int32_t* pos,
+                                      int32_t* len, const void* k_seq, const void* v_seq, const int32_t* pos_seq,
+                                      int32_t n_steps, int32_t max_len_first, float softmax_scale, void* out_seq,
+                                      void* workspace, size_t workspace_bytes, void* stream) {
+    fk_status s = check_desc(desc);
+    if (s != FK_OK) return s;
+    if (n_steps < 0 || max_len_first <= 0 || max_len_first > desc->capacity) return FK_ERR_INVALID_ARG;
+    if (!q_seq || !k_seq || !v_seq || !pos_seq || !out_seq) return FK_ERR_INVALID_ARG;
+    const size_t e = desc->dtype == FK_F32 ? 4 : 2;
+    const size_t q_step = (size_t)desc->batch * desc->n_q_heads * desc->head_dim * e;   // bytes per step, multiples of 16
+    const size_t kv_step = (size_t)desc->batch * desc->n_kv_heads * desc->head_dim * e;
+    for (int32_t t = 0; t < n_steps; ++t) {
+        const int64_t ml = (int64_t)max_len_first + t;
+        s = fk_decode_step(desc, static_cast<const char*>(q_seq) + t * q_step, K, V, pos, len,
+                           static_cast<const char*>(k_seq) + t * kv_step, static_cast<const char*>(v_seq) + t * kv_step,
+                           pos_seq + (size_t)t * desc->batch, ml > desc->capacity ? desc->capacity : (int32_t)ml, softmax_scale,
+                           static_cast<char*>(out_seq) + t * q_step, workspace, workspace_bytes, stream);
+        if (s != FK_OK) return s;
+    }
+    return FK_OK;
 }
 
 extern "C" size_t fk_decode_step_feat_workspace(const fk_cache_desc* desc) {

@@ -23,25 +23,32 @@ namespace fk {
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
 typedef __attribute__((ext_vector_type(16))) float f32x16_t;
 
-static constexpr int kScoreThreads = 1024;  // four wavefronts per SIMD: MFMAs of one overlap the gelu of the others
+#ifndef FK_SCORE_NT
+#define FK_SCORE_NT 1
+#endif
+#ifndef FK_SCORE_THREADS
+#define FK_SCORE_THREADS 1024
+#endif
+// NT pair tiles share every LDS read of a W1^T operand; several wavefronts per SIMD so that the MFMAs of one
+// overlap the gelu of the others
+static constexpr int kScoreNT = FK_SCORE_NT;
+static constexpr int kScoreThreads = FK_SCORE_THREADS;
 static constexpr int kScoreWaves = kScoreThreads / kWave;
 static constexpr int kWPad = 8;  // bf16 elements of padding per transposed W1 row in LDS
 
-// gelu(z) = z Phi(z) = 0.5 z + 0.5 |z| erf(|z| / sqrt 2), erf by the Abramowitz-Stegun rational
-// form 7.1.26 (|error| < 1.5e-7 on erf, < 5e-7 on gelu): one reciprocal, one exp2, 9 FMA/mul.
+// gelu(z) = z Phi(z) = max(z, 0) - |z| Phi(-|z|) with the lower normal tail as Phi(-a) = 2^P(a), P a quintic
+// fitted to log2 Phi(-a) on a >= 0 (weighted minimax on the error of gelu; the leading coefficient is negative,
+// so the tail keeps falling beyond the fitted range).  |error| <= 6.4e-7 on gelu over all finite z (checked against
+// the erf form in double precision on a 1e-5 grid over [-40, 40]); five FMAs, one exp2, one median-of-three, one FMA.
 // The scorer's epilogue is bound by this function, not by the MFMAs.
 __device__ __forceinline__ float gelu_erf(float z) {
-    const float az = fabsf(z);
-    const float u = az * 0.70710678118654752f;
-    const float t = __builtin_amdgcn_rcpf(fmaf(0.3275911f, u, 1.0f));
-    float p = fmaf(1.061405429f, t, -1.453152027f);
-    p = fmaf(p, t, 1.421413741f);
-    p = fmaf(p, t, -0.284496736f);
-    p = fmaf(p, t, 0.254829592f);
-    p *= t;
-    const float e = __builtin_amdgcn_exp2f(-(u * u) * 1.4426950408889634f);
-    const float erf_abs = fmaf(-p, e, 1.0f);
-    return fmaf(0.5f * az, erf_abs, 0.5f * z);
+    const float a = fabsf(z);
+    float p = fmaf(-4.733092552e-04f, a, 7.084556704e-03f);
+    p = fmaf(p, a, -5.182738105e-02f);
+    p = fmaf(p, a, -4.599924418e-01f);
+    p = fmaf(p, a, -1.150787850e+00f);
+    p = fmaf(p, a, -1.000037623e+00f);
+    return fmaf(-a, __builtin_amdgcn_exp2f(p), __builtin_amdgcn_fmed3f(z, 0.f, __builtin_inff()));  // med3 = max(z, 0), one instruction
 }
 
 // reference-accuracy form for the fp32 path
@@ -83,7 +90,8 @@ __global__ __launch_bounds__(kScoreThreads) void score_mfma_kernel(
     const int n = min(len[row], cap);
     const int p_begin = blockIdx.x * pairs_per_block;
     if (p_begin >= n || n <= skip_len) return;
-    const int p_end = min(p_begin + pairs_per_block, n);
+    // the last workgroup of a row runs on to the row's end (a max_len hint below len[row] costs time, not scores)
+    const int p_end = blockIdx.x == gridDim.x - 1 ? n : min(p_begin + pairs_per_block, n);
     const int hw = per_head ? hkv : 0;
 
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
@@ -193,11 +201,23 @@ __global__ __launch_bounds__(kScoreThreads) void score_mfma_kernel(
         for (int t = 0; t < NT; ++t) phi[t] = 0.f;
 
         for (int ht = 0; ht < HP / 32; ++ht) {
+            // C layout: element i of a lane is hidden unit ht*32 + (i/4)*8 + half*4 + i%4; the accumulators
+            // start from the bias of their hidden unit
             f32x16_t acc[NT];
+            float4 ww[4];
 #pragma unroll
-            for (int t = 0; t < NT; ++t)
+            for (int i4 = 0; i4 < 4; ++i4) {
+                const int j = ht * 32 + i4 * 8 + half * 4;
+                const float4 bb = *reinterpret_cast<const float4*>(s_b1 + j);
+                ww[i4] = *reinterpret_cast<const float4*>(s_w2 + j);
 #pragma unroll
-                for (int i = 0; i < 16; ++i) acc[t][i] = 0.f;
+                for (int t = 0; t < NT; ++t) {
+                    acc[t][i4 * 4 + 0] = bb.x;
+                    acc[t][i4 * 4 + 1] = bb.y;
+                    acc[t][i4 * 4 + 2] = bb.z;
+                    acc[t][i4 * 4 + 3] = bb.w;
+                }
+            }
             const bf16_t* wrow = s_wt + (size_t)(ht * 32 + l32) * FS + half * 8;
 #pragma unroll
             for (int ks = 0; ks < KS; ++ks) {
@@ -219,18 +239,14 @@ __global__ __launch_bounds__(kScoreThreads) void score_mfma_kernel(
                     }
                 }
             }
-            // C layout: element i of a lane is hidden unit ht*32 + (i/4)*8 + half*4 + i%4
 #pragma unroll
             for (int i4 = 0; i4 < 4; ++i4) {
-                const int j = ht * 32 + i4 * 8 + half * 4;
-                const float4 bb = *reinterpret_cast<const float4*>(s_b1 + j);
-                const float4 ww = *reinterpret_cast<const float4*>(s_w2 + j);
 #pragma unroll
                 for (int t = 0; t < NT; ++t) {
-                    phi[t] = fmaf(gelu_erf(acc[t][i4 * 4 + 0] + bb.x), ww.x, phi[t]);
-                    phi[t] = fmaf(gelu_erf(acc[t][i4 * 4 + 1] + bb.y), ww.y, phi[t]);
-                    phi[t] = fmaf(gelu_erf(acc[t][i4 * 4 + 2] + bb.z), ww.z, phi[t]);
-                    phi[t] = fmaf(gelu_erf(acc[t][i4 * 4 + 3] + bb.w), ww.w, phi[t]);
+                    phi[t] = fmaf(gelu_erf(acc[t][i4 * 4 + 0]), ww[i4].x, phi[t]);
+                    phi[t] = fmaf(gelu_erf(acc[t][i4 * 4 + 1]), ww[i4].y, phi[t]);
+                    phi[t] = fmaf(gelu_erf(acc[t][i4 * 4 + 2]), ww[i4].z, phi[t]);
+                    phi[t] = fmaf(gelu_erf(acc[t][i4 * 4 + 3]), ww[i4].w, phi[t]);
                 }
             }
         }
@@ -263,7 +279,6 @@ __global__ __launch_bounds__(kSimpleWaves * kWave) void score_simple_kernel(
     const int n = min(len[row], cap);
     if (n <= skip_len) return;
     const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
-    const int p0 = (blockIdx.x * kSimpleWaves + wave) * PP;
     const int hw = per_head ? hkv : 0;
     const int A = feat ? kFeatPlanes * g : 0;  // attention features behind k and v
     const int F = 2 * D + A;
@@ -274,50 +289,56 @@ __global__ __launch_bounds__(kSimpleWaves * kWave) void score_simple_kernel(
         else return __uint_as_float(((uint32_t)*ptr) << 16);
     };
     float* x = s_x + (size_t)wave * PP * F;
-    if (p0 < n) {
-        for (int p = 0; p < PP; ++p) {
-            const int pair = min(p0 + p, n - 1);
-            const T* krow = K + ((size_t)row * cap + pair) * D;
-            const T* vrow = V + ((size_t)row * cap + pair) * D;
-            for (int f = lane; f < 2 * D; f += kWave) x[p * F + f] = f < D ? widen(krow + f) : widen(vrow + f - D);
-            for (int a = lane; a < A; a += kWave) {  // feature a = head * 6 + plane; carried planes include this chunk
-                const int head = a / kFeatPlanes, pl = a % kFeatPlanes;
-                const float* fp = feat + (size_t)row * kFeatPlanes * cap * GP + (size_t)pair * GP + head;
-                const size_t plane = (size_t)cap * GP;
-                float v = fp[pl * plane];
-                if (pl == 4) v += fp[3 * plane];
-                if (pl == 5) v = fmaf(kFeatDecay, v, fp[3 * plane]);
-                x[p * F + 2 * D + a] = v;
+    const float bias2 = b2[hw];
+    // the grid covers max_len pairs; rows longer than that are finished by further rounds of the same workgroups
+    for (int pb = blockIdx.x * kSimpleWaves * PP; pb < n; pb += gridDim.x * kSimpleWaves * PP) {
+        const int p0 = pb + wave * PP;
+        if (p0 < n) {
+            for (int p = 0; p < PP; ++p) {
+                const int pair = min(p0 + p, n - 1);
+                const T* krow = K + ((size_t)row * cap + pair) * D;
+                const T* vrow = V + ((size_t)row * cap + pair) * D;
+                for (int f = lane; f < 2 * D; f += kWave) x[p * F + f] = f < D ? widen(krow + f) : widen(vrow + f - D);
+                for (int a = lane; a < A; a += kWave) {  // feature a = head * 6 + plane; carried planes include this chunk
+                    const int head = a / kFeatPlanes, pl = a % kFeatPlanes;
+                    const float* fp = feat + (size_t)row * kFeatPlanes * cap * GP + (size_t)pair * GP + head;
+                    const size_t plane = (size_t)cap * GP;
+                    float v = fp[pl * plane];
+                    if (pl == 4) v += fp[3 * plane];
+                    if (pl == 5) v = fmaf(kFeatDecay, v, fp[3 * plane]);
+                    x[p * F + 2 * D + a] = v;
+                }
             }
         }
-    }
-    __syncthreads();
-    if (p0 >= n) return;
-    float phi[PP];
+        __syncthreads();
+        if (p0 < n) {
+            float phi[PP];
 #pragma unroll
-    for (int p = 0; p < PP; ++p) phi[p] = 0.f;
-    for (int j = lane; j < (H + kWave - 1) / kWave * kWave; j += kWave) {
-        const bool live = j < H;
-        const T* wj = w + (live ? j : 0);
-        float z[PP];
+            for (int p = 0; p < PP; ++p) phi[p] = 0.f;
+            for (int j = lane; j < (H + kWave - 1) / kWave * kWave; j += kWave) {
+                const bool live = j < H;
+                const T* wj = w + (live ? j : 0);
+                float z[PP];
 #pragma unroll
-        for (int p = 0; p < PP; ++p) z[p] = 0.f;
-        for (int f = 0; f < F; ++f) {
-            const float wv = widen(wj + (size_t)f * H);
+                for (int p = 0; p < PP; ++p) z[p] = 0.f;
+                for (int f = 0; f < F; ++f) {
+                    const float wv = widen(wj + (size_t)f * H);
 #pragma unroll
-            for (int p = 0; p < PP; ++p) z[p] = fmaf(x[p * F + f], wv, z[p]);
+                    for (int p = 0; p < PP; ++p) z[p] = fmaf(x[p * F + f], wv, z[p]);
+                }
+                if (live) {
+                    const float bb = b1[(size_t)hw * H + j], ww = W2[(size_t)hw * H + j];
+#pragma unroll
+                    for (int p = 0; p < PP; ++p) phi[p] = fmaf(gelu_erf_precise(z[p] + bb), ww, phi[p]);
+                }
+            }
+#pragma unroll
+            for (int p = 0; p < PP; ++p) {
+                const float tot = group_sum<64>(phi[p]);
+                if (lane == 0 && p0 + p < n) scores[(size_t)row * cap + p0 + p] = tot + bias2;
+            }
         }
-        if (live) {
-            const float bb = b1[(size_t)hw * H + j], ww = W2[(size_t)hw * H + j];
-#pragma unroll
-            for (int p = 0; p < PP; ++p) phi[p] = fmaf(gelu_erf_precise(z[p] + bb), ww, phi[p]);
-        }
-    }
-    const float bias2 = b2[hw];
-#pragma unroll
-    for (int p = 0; p < PP; ++p) {
-        const float tot = group_sum<64>(phi[p]);
-        if (lane == 0 && p0 + p < n) scores[(size_t)row * cap + p0 + p] = tot + bias2;
+        __syncthreads();  // the staged inputs are free for the next round
     }
 }
 
@@ -331,7 +352,7 @@ static size_t score_lds_bytes(int D, int H, int gf = 0) {
 template <int D, int GF>
 static fk_status score_mfma_launch(const fk_cache_desc* d, const void* K, const void* V, const float* feat,
                                    const int32_t* len, int max_len, const fk_scorer* sc, float* scores, hipStream_t st) {
-    constexpr int NT = 1;
+    constexpr int NT = kScoreNT;
     const int rows = d->batch * d->n_kv_heads;
     const size_t lds = score_lds_bytes(D, sc->hidden, GF);
     // pairs per workgroup: fill the chip about once, in whole wave tiles

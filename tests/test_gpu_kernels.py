@@ -129,6 +129,13 @@ SCORE_SHAPES = [
     ("f32", 128, 20, 1, 70, [70], True),
     ("bf16", 128, 16, 8, 2176, [2176, 1500], True),    # the paper's hidden width (Section 4.1): padded to one MFMA tile
     ("bf16", 128, 48, 2, 300, [300, 31], True),        # a width that is no multiple of 32
+    # more widths: hidden tiles partly empty, shared weights, rows that end inside a tile / a workgroup's share
+    ("bf16", 128, 72, 2, 700, [700, 33], True),
+    ("bf16", 128, 128, 2, 1100, [1100, 1087, 32], False),
+    ("bf16", 128, 200, 3, 520, [520, 97], True),
+    ("bf16", 64, 256, 2, 1300, [1300, 64], True),
+    ("bf16", 64, 136, 2, 300, [300, 299], False),
+    ("bf16", 64, 512, 1, 200, [200], True),
 ]
 
 
