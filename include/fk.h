@@ -126,6 +126,23 @@ fk_status fk_decode_step(const fk_cache_desc *desc, const void *q, void *K, void
                          size_t workspace_bytes, void *stream);
 
 /*
+ * fk_decode_step for callers that cannot allocate device memory (code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc): same arguments and results as fk_decode_step without the workspace,
+ * which is a fixed FK_STATIC_SCRATCH_BYTES array inside the library's device image (each GPU the library runs on
+ * holds its own copy until the process ends).  FK_ERR_WORKSPACE when fk_decode_attn_workspace(desc, max_len)
+ * exceeds FK_STATIC_SCRATCH_BYTES (about batch * n_kv_heads * splits * g * (head_dim + 2) * 4 bytes; the Qwen3-4B
+ * layer shape at batch 16 needs 0.8 MB); FK_ERR_LAUNCH if the array's address cannot be resolved.  Nothing is
+ * allocated or freed, by this call or by anything it calls.  The first call on a device looks the array up and
+ * clears it with a small kernel on `stream` (make that call outside a graph capture); every call leaves the
+ * counters in it at zero for the next one.  All calls on one GPU share the array: calls that overlap in time
+ * on one GPU (two streams, two threads) race, the caller must serialise them.
+ */
+#define FK_STATIC_SCRATCH_BYTES (8u << 20)
+fk_status fk_decode_step_static(const fk_cache_desc *desc, const void *q, void *K, void *V, int32_t *pos,
+                                int32_t *len, const void *k_new, const void *v_new, const int32_t *pos_new,
+                                int32_t max_len, float softmax_scale, void *out, void *stream);
+
+/*
  * Section 3.1 (the L generation steps between two eviction events): n_steps consecutive fk_decode_step calls
  * enqueued by one call, step t on q_seq[t], k_seq[t], v_seq[t], pos_seq[t] with its output in out_seq[t] and
  * max_len = min(max_len_first + t, capacity); max_len_first bounds len[r] + 1 at the first step.

@@ -19,7 +19,7 @@ LIB_PATH = os.path.join(_HERE, "libfk.so")
 FK_OK, FK_ERR_INVALID_ARG, FK_ERR_UNSUPPORTED, FK_ERR_WORKSPACE, FK_ERR_LAUNCH = range(5)
 FK_F32, FK_BF16 = 0, 1
 
-SYMBOLS = ["fk_status_string", "fk_version", "fk_append", "fk_decode_attn_workspace", "fk_decode_attn", "fk_decode_step", "fk_decode_window",
+SYMBOLS = ["fk_status_string", "fk_version", "fk_append", "fk_decode_attn_workspace", "fk_decode_attn", "fk_decode_step", "fk_decode_window", "fk_decode_step_static",
            "fk_score_kv", "fk_select_keep", "fk_select_keep_sampled", "fk_compact", "fk_decode_step_feat_workspace",
            "fk_decode_step_feat", "fk_score_kv_feat", "fk_compact_feat", "fk_golden_steps", "fk_golden_scores",
            "fk_golden_trace", "fk_stream_read"]
@@ -60,6 +60,7 @@ def lib() -> ctypes.CDLL:
         L.fk_decode_attn.restype, L.fk_decode_attn.argtypes = ctypes.c_int, [dp, vp, vp, vp, vp, i32, f32, vp, vp, sz, vp]
         L.fk_decode_step.restype, L.fk_decode_step.argtypes = ctypes.c_int, [dp, vp, vp, vp, vp, vp, vp, vp, vp, i32, f32, vp, vp, sz, vp]
         L.fk_decode_window.restype, L.fk_decode_window.argtypes = ctypes.c_int, [dp, vp, vp, vp, vp, vp, vp, vp, vp, i32, i32, f32, vp, vp, sz, vp]
+        L.fk_decode_step_static.restype, L.fk_decode_step_static.argtypes = ctypes.c_int, [dp, vp, vp, vp, vp, vp, vp, vp, vp, i32, f32, vp, vp]
         L.fk_score_kv.restype, L.fk_score_kv.argtypes = ctypes.c_int, [dp, vp, vp, vp, i32, sp, vp, vp]
         L.fk_select_keep.restype, L.fk_select_keep.argtypes = ctypes.c_int, [dp, vp, vp, vp, i32, i32, i32, vp, vp]
         L.fk_select_keep_sampled.restype, L.fk_select_keep_sampled.argtypes = ctypes.c_int, [dp, vp, vp, vp, vp, i32, i32, i32, i32, vp, vp]
@@ -149,6 +150,14 @@ def fk_decode_step(desc: CacheDesc, q, K, V, pos, length, k_new, v_new, pos_new,
     _check(lib().fk_decode_step(ctypes.byref(desc.c()), _ptr(q), _ptr(K), _ptr(V), _ptr(pos), _ptr(length), _ptr(k_new),
                                 _ptr(v_new), _ptr(pos_new), int(max_len), float(softmax_scale), _ptr(out),
                                 _ptr(workspace), nbytes, _stream(stream)), "fk_decode_step")
+
+
+def fk_decode_step_static(desc: CacheDesc, q, K, V, pos, length, k_new, v_new, pos_new, max_len: int, softmax_scale: float,
+                          out, stream=None) -> None:
+    """fk_decode_step on the library's own fixed scratch: no workspace argument, nothing allocated."""
+    _check(lib().fk_decode_step_static(ctypes.byref(desc.c()), _ptr(q), _ptr(K), _ptr(V), _ptr(pos), _ptr(length), _ptr(k_new),
+                                       _ptr(v_new), _ptr(pos_new), int(max_len), float(softmax_scale), _ptr(out),
+                                       _stream(stream)), "fk_decode_step_static")
 
 
 def fk_decode_window(desc: CacheDesc, q_seq, K, V, pos, length, k_seq, v_seq, pos_seq, n_steps: int, max_len_first: int,

@@ -28,6 +28,7 @@
 // and normaliser known, a second pass turns them into attention weights and adds them to the open
 // planes of the row's feature state.
 #include "fk_common.h"
+#include <mutex>
 
 namespace fk {
 
@@ -940,6 +941,53 @@ extern "C" fk_status fk_decode_window(const fk_cache_desc* desc, const void* q_s
         if (s != FK_OK) return s;
     }
     return FK_OK;
+}
+
+// ---------------------------------------------------------------------------------------------------------
+// fk_decode_step_static: fk_decode_step for callers that cannot allocate.  The workspace (row arrival counters
+// and split records) is a fixed array in the library's device image; every GPU the library runs on holds
+// its own copy at its own address, looked up once per device.
+// ---------------------------------------------------------------------------------------------------------
+namespace fk {
+static constexpr size_t kStaticScratchBytes = FK_STATIC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+static void* g_scratch_ptr[kMaxDevices] = {};  // device address of `scratch` on each device, null until looked up
+static std::mutex g_scratch_mutex;
+
+__global__ void scratch_clear_kernel(uint4* p, size_t n16) {
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += stride) p[i] = make_uint4(0, 0, 0, 0);
+}
+
+// Device address of the static scratch on the current device; on the first call on a device the address is looked
+// up and the array is cleared on `st` (a fill kernel, no memset node: the caller may be capturing a graph), which
+// orders the clear before the first launch that uses it.  Null on failure.
+static void* static_scratch(hipStream_t st) {
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void* ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) return nullptr;
+        hipLaunchKernelGGL(scratch_clear_kernel, dim3(256), dim3(256), 0, st, reinterpret_cast<uint4*>(ptr), kStaticScratchBytes / 16);
+        if (hipGetLastError() != hipSuccess) return nullptr;
+        g_scratch_ptr[dev] = ptr;
+    }
+    return g_scratch_ptr[dev];
+}
+}  // namespace fk
+
+extern "C" fk_status fk_decode_step_static(const fk_cache_desc* desc, const void* q, void* K, void* V, int32_t* pos,
+                                           int32_t* len, const void* k_new, const void* v_new, const int32_t* pos_new,
+                                           int32_t max_len, float softmax_scale, void* out, void* stream) {
+    fk_status s = check_desc(desc);
+    if (s != FK_OK) return s;
+    if (max_len <= 0 || max_len > desc->capacity) return FK_ERR_INVALID_ARG;
+    if (fk_decode_attn_workspace(desc, max_len) > kStaticScratchBytes) return FK_ERR_WORKSPACE;  // beyond the fixed scratch
+    if (!q || !K || !V || !pos || !len || !k_new || !v_new || !pos_new || !out) return FK_ERR_INVALID_ARG;
+    void* ws = static_scratch((hipStream_t)stream);
+    if (!ws) return FK_ERR_LAUNCH;
+    return fk_decode_step(desc, q, K, V, pos, len, k_new, v_new, pos_new, max_len, softmax_scale, out, ws, kStaticScratchBytes, stream);
 }
 
 extern "C" size_t fk_decode_step_feat_workspace(const fk_cache_desc* desc) {
