@@ -173,7 +173,7 @@ fk_status fk_score_kv(const fk_cache_desc *desc, const void *K, const void *V, c
  * budget - protect_recent best under the total order (score descending, then slot
  * ascending = position ascending).  -0 equals +0; NaN ranks below -inf.  The kept slot
  * indices are written ascending to keep_idx[b][h][0 .. budget-1].  Rows with
- * len[r] <= budget get keep_idx[j] = j for j < len[r]; the rest of their row is not written.
+ * len[r] <= budget get the identity keep_idx[j] = j for all j < budget (nothing to prune; fk_compact moves nothing).
  * keep_idx: [batch][n_kv_heads][budget] int32.  pos may be NULL: it is not read, slot order
  * stands for position order (see the precondition above).
  * Requires 0 <= protect_recent <= budget <= capacity.
@@ -191,7 +191,7 @@ fk_status fk_select_keep(const fk_cache_desc *desc, const float *scores, const i
  * noise[b][h][i] (iid Gumbel(0,1) for the paper's law; fp32, [batch][n_kv_heads][capacity]) and the
  * E candidates with the smallest fp32 value of scores - noise are evicted, ties evicting the higher
  * slot first.  noise == 0 or n_candidates <= E gives fk_select_keep's result.  Output, rows at or
- * under budget, pos and the special values are as for fk_select_keep.  max_len <= 131072
+ * under budget, pos and the special values are as for fk_select_keep.  capacity <= 131072
  * (FK_ERR_UNSUPPORTED above).
  */
 fk_status fk_select_keep_sampled(const fk_cache_desc *desc, const float *scores, const float *noise,
@@ -204,6 +204,9 @@ fk_status fk_select_keep_sampled(const fk_cache_desc *desc, const float *scores,
  * with len[r] > budget, slot j of K, V and pos receives the former contents of slot
  * keep_idx[b][h][j], j = 0 .. budget-1 (bit copies; keep_idx ascending with keep_idx[j] >= j,
  * as fk_select_keep writes it), then len[r] = budget.  Rows with len[r] <= budget are untouched.
+ * What moves is read from keep_idx alone (one launch, the length is clamped in the same kernel): every row of
+ * keep_idx must be written in full, rows at or under budget with the identity or with entries outside
+ * [0, capacity) (both move nothing; fk_select_keep and fk_select_keep_sampled write the identity).
  */
 fk_status fk_compact(const fk_cache_desc *desc, void *K, void *V, int32_t *pos, int32_t *len,
                      const int32_t *keep_idx, int32_t budget, void *stream);

@@ -17,6 +17,23 @@ __device__ __forceinline__ uint32_t score_key(float s) {
     return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
 }
 
+// Inclusive prefix sum over the 64 lanes of a wavefront with data-parallel-primitive moves (a handful of cycles per
+// step; the same scan through LDS permutes costs about a hundred per step): shifts by 1, 2, 4, 8 inside each row of 16
+// lanes, then the last lane of rows 0 / 2 is added to rows 1 / 3, then lane 31 to the upper half.
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ uint32_t dpp_u32(uint32_t v) {
+    return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, CTRL, ROW_MASK, 0xF, false);  // lanes without a source get 0
+}
+__device__ __forceinline__ uint32_t wave_scan_incl(uint32_t v) {
+    v += dpp_u32<0x111, 0xF>(v);  // row_shr:1
+    v += dpp_u32<0x112, 0xF>(v);  // row_shr:2
+    v += dpp_u32<0x114, 0xF>(v);  // row_shr:4
+    v += dpp_u32<0x118, 0xF>(v);  // row_shr:8
+    v += dpp_u32<0x142, 0xA>(v);  // row_bcast:15 into rows 1 and 3
+    v += dpp_u32<0x143, 0xC>(v);  // row_bcast:31 into rows 2 and 3
+    return v;
+}
+
 // inclusive scan of a 64-bit value over the workgroup, in thread order; returns the inclusive
 // value and the workgroup total.  s_part must hold kSelWaves entries.
 __device__ __forceinline__ unsigned long long block_scan_incl(unsigned long long v,

@@ -72,3 +72,21 @@ def assert_scores_close(got, ref, lens, what=""):
             bound = 1e-3 * np.maximum(np.abs(r), np.sqrt(np.mean(r * r)))
             bad = np.abs(g - r) > bound
             assert not bad.any(), f"{what} row ({b},{h}): {bad.sum()} scores off, worst {np.abs(g - r).max():.3e} vs bound {bound.min():.3e}"
+
+
+def assert_keep_equal(got, ref, lens, budget, what=""):
+    """Keep-sets bit for bit.  Rows over budget: the device's kept slots equal the oracle's.  Rows at or under budget
+    (nothing to prune): the device writes the identity over all `budget` entries, the oracle j for j < len and -1
+    beyond; both say "every live slot stays where it is"."""
+    got, ref = np.asarray(got), np.asarray(ref)
+    assert got.shape == ref.shape and got.shape[-1] == budget
+    Bt, Hkv, _ = ref.shape
+    ident = np.arange(budget, dtype=ref.dtype)
+    for b in range(Bt):
+        n = int(lens[b])
+        for h in range(Hkv):
+            if n > budget:
+                assert np.array_equal(got[b, h], ref[b, h]), f"{what} row ({b},{h}): keep-set differs"
+            else:
+                assert np.array_equal(ref[b, h, :n], ident[:n]) and (ref[b, h, n:] == -1).all(), f"{what} row ({b},{h}): oracle convention"
+                assert np.array_equal(got[b, h], ident), f"{what} row ({b},{h}): identity expected at or under budget"

@@ -112,7 +112,7 @@ def test_rows_of_a_sequence_may_hold_different_counts(gpu, ora):
     keep_ref = ora.select_keep(sc, c.pos, c.len, budget, recent, "sort")
     keep = torch.full((Bt, Hkv, budget), -1, dtype=torch.int32, device="cuda")
     fk.fk_select_keep(desc, gpu.to_dev(sc.reshape(Bt, Hkv, cap)), pos, ln, cap, budget, recent, keep)
-    assert np.array_equal(keep.cpu().numpy().reshape(keep_ref.shape), keep_ref)
+    gpu.assert_keep_equal(keep.cpu().numpy().reshape(keep_ref.shape), keep_ref, c.len, budget, "per-row lengths")
     fk.fk_compact(desc, K, V, pos, ln, keep, budget)
     ora.compact(c, keep_ref, budget)
     assert np.array_equal(gpu.to_host(ln).reshape(-1), c.len)
@@ -195,7 +195,7 @@ def test_select_keep_bit_exact(gpu, ora, Bt, Hkv, cap, lens, budget, recent, tie
     desc = fk.CacheDesc(Bt, Hkv, Hkv, 128, cap, "bf16")
     keep = torch.full((Bt, Hkv, budget), -1, dtype=torch.int32, device="cuda")
     fk.fk_select_keep(desc, gpu.to_dev(sc), gpu.to_dev(pos), gpu.to_dev(np.repeat(ln[:, None], Hkv, 1)), cap, budget, recent, keep)
-    assert np.array_equal(keep.cpu().numpy(), ref)
+    gpu.assert_keep_equal(keep.cpu().numpy(), ref, ln, budget)
 
 
 def test_select_keep_special_values(gpu, ora):
@@ -214,7 +214,7 @@ def test_select_keep_special_values(gpu, ora):
     desc = fk.CacheDesc(1, 4, 4, 128, cap, "bf16")
     keep = torch.full((1, 4, budget), -1, dtype=torch.int32, device="cuda")
     fk.fk_select_keep(desc, gpu.to_dev(sc), None, gpu.to_dev(np.repeat(ln[:, None], 4, 1)), cap, budget, recent, keep)
-    assert np.array_equal(keep.cpu().numpy(), ref)
+    gpu.assert_keep_equal(keep.cpu().numpy(), ref, ln, budget)
     assert keep[0, 3].cpu().tolist() == list(range(600)) + list(range(1100, 1200))
 
 
@@ -247,7 +247,7 @@ def test_select_keep_sampled_bit_exact(gpu, ora, Bt, Hkv, cap, lens, budget, rec
     keep = torch.full((Bt, Hkv, budget), -1, dtype=torch.int32, device="cuda")
     dln = gpu.to_dev(np.repeat(ln[:, None], Hkv, 1))
     fk.fk_select_keep_sampled(desc, gpu.to_dev(sc), gpu.to_dev(noise), gpu.to_dev(pos), dln, cap, budget, recent, n_cand, keep)
-    assert np.array_equal(keep.cpu().numpy(), ref)
+    gpu.assert_keep_equal(keep.cpu().numpy(), ref, ln, budget)
     # zero noise: the deterministic entry point's answer
     det = torch.full_like(keep, -1)
     fk.fk_select_keep(desc, gpu.to_dev(sc), None, dln, cap, budget, recent, det)
@@ -368,16 +368,9 @@ def test_select_and_compact_random_shapes(gpu, ora):
         ref_s = ora.select_keep_sampled(sc, noise, c.pos, c.len, budget, recent, n_cand)
         fk.fk_select_keep(dev.desc, dsc, dev.pos, dev.len, cap, budget, recent, keep)
         ref = ora.select_keep(sc, c.pos, c.len, budget, recent, "sort")
-        got = keep.cpu().numpy()
-        for b in range(Bt):
-            n = lens[b]
-            m = budget if n > budget else n          # rows at or under budget: identity over the live slots
-            assert np.array_equal(got[b, :, :m], ref[b, :, :m]), f"case {case} row {b}"
+        gpu.assert_keep_equal(keep.cpu().numpy(), ref, lens, budget, f"case {case}")
         fk.fk_select_keep_sampled(dev.desc, dsc, dnz, dev.pos, dev.len, cap, budget, recent, n_cand, keep)
-        got_s = keep.cpu().numpy()
-        for b in range(Bt):
-            m = budget if lens[b] > budget else lens[b]
-            assert np.array_equal(got_s[b, :, :m], ref_s[b, :, :m]), f"case {case} row {b} (sampled)"
+        gpu.assert_keep_equal(keep.cpu().numpy(), ref_s, lens, budget, f"case {case} (sampled)")
         fk.fk_compact(dev.desc, dev.K, dev.V, dev.pos, dev.len, keep, budget)
         ora.compact(c, ref_s, budget)
         host = dev.host(ora)

@@ -137,6 +137,60 @@ def test_qwen3_4b_layer_shape_sampled_rows(gpu, ora):
                         fused=scale == w.softmax_scale) >= 2
 
 
+def test_qwen3_4b_layer_all_rows_around_an_event(gpu, ora):
+    """configs[1] at the steady state bench.py times (batch 16, 32/8 heads, D 128, bf16, B 2048, L 128, rows at
+    B + L - 2 pairs): EVERY one of the 128 rows is compared with the oracle for the two decode steps before an
+    eviction event (enqueued by one fk_decode_window call, as bench.py does), the event itself (scores; keep-sets on
+    the oracle's scores and on the device's own; K, V, positions and lengths after the compaction, bit for bit)
+    and the two steps after it."""
+    import paper_2602_03203_amd as fk
+    w = si.config(1)
+    B, L, g, Bt, Hkv = w.budget, w.interval, w.group, w.batch, w.n_kv_heads
+    start = B + L - 2
+    lens0 = np.full(Bt, start, np.int32)
+    print("all rows: building the cache", flush=True)
+    c = workload_cache(ora, w, lens=lens0)
+    dev = gpu.DevCache(c, w.n_q_heads)
+    W = scorer_storage(w)
+    dW = [gpu.to_dev(x) for x in W]
+    q, k, v, p = bulk_step_inputs(w, 0, 0, 4, lens0)
+    dq, dk, dv, dp = (gpu.to_dev(x) for x in (q, k, v, p))
+    outs = torch.empty((4, Bt, w.n_q_heads, w.head_dim), dtype=torch.bfloat16, device="cuda")
+    for scale in (w.softmax_scale, 128.0 ** 0.5):   # near-uniform and unit-variance logits, each on a fresh copy
+        cc = c.copy()
+        d2 = gpu.DevCache(cc, w.n_q_heads)
+        fk.fk_decode_window(d2.desc, dq[:2], d2.K, d2.V, d2.pos, d2.len, dk[:2], dv[:2], dp[:2], 2, start + 1, scale, outs[:2], d2.ws)
+        for t in range(2):
+            ora.append(cc, k[t], v[t], p[t])
+            gpu.assert_attn_close(gpu.out_to_f64(outs[t]), ora.decode_attn(cc, q[t], scale), "bf16", f"scale {scale:.3f} step {t}")
+        assert int(d2.len.min()) == B + L == int(d2.len.max())
+        print("all rows: event", flush=True)
+        fk.fk_score_kv(d2.desc, d2.K, d2.V, d2.len, B + L, *dW, d2.scores, skip_len=B)
+        sc = ora.score_kv(cc, *W)
+        own = d2.scores.cpu().numpy()
+        gpu.assert_scores_close(own, sc, cc.len, "all rows scores")
+        keep = torch.full((Bt, Hkv, B), -1, dtype=torch.int32, device="cuda")
+        fk.fk_select_keep(d2.desc, d2.scores, d2.pos, d2.len, B + L, B, L, keep)          # on the device's own scores
+        gpu.assert_keep_equal(keep.cpu().numpy(), ora.select_keep(own, cc.pos, cc.len, B, L, "sort"), cc.len, B, "own scores")
+        sc32 = sc.astype(np.float32)
+        keep_ref = ora.select_keep(sc32, cc.pos, cc.len, B, L, "sort")
+        d2.scores.copy_(torch.from_numpy(sc32).cuda())
+        fk.fk_select_keep(d2.desc, d2.scores, d2.pos, d2.len, B + L, B, L, keep)          # on the oracle's scores
+        gpu.assert_keep_equal(keep.cpu().numpy(), keep_ref, cc.len, B, "oracle scores")
+        fk.fk_compact(d2.desc, d2.K, d2.V, d2.pos, d2.len, keep, B)
+        ora.compact(cc, keep_ref, B)
+        h = d2.host(ora)
+        assert np.array_equal(h.len, cc.len) and (h.len == B).all()
+        assert np.array_equal(h.pos[:, :, :B], cc.pos[:, :, :B])
+        assert np.array_equal(h.K[:, :, :B], cc.K[:, :, :B]) and np.array_equal(h.V[:, :, :B], cc.V[:, :, :B])
+        fk.fk_decode_window(d2.desc, dq[2:], d2.K, d2.V, d2.pos, d2.len, dk[2:], dv[2:], dp[2:], 2, B + 1, scale, outs[2:], d2.ws)
+        for t in range(2, 4):
+            ora.append(cc, k[t], v[t], p[t])
+            gpu.assert_attn_close(gpu.out_to_f64(outs[t]), ora.decode_attn(cc, q[t], scale), "bf16", f"scale {scale:.3f} step {t}")
+        assert int(d2.len.min()) == B + 2 == int(d2.len.max())
+    del dev
+
+
 def test_gqa7_mixture_sampled_rows(gpu, ora):
     """configs[3] shapes (28/4 heads, D 128, B 4096, L 64) with duplicate-heavy keys: exact score ties."""
     w = si.config(3).scaled(layers=1, batch=4, prompt=4096 - 64)
@@ -205,7 +259,7 @@ def test_one_shot_prefill_compression(gpu, ora):
     dev.scores.copy_(torch.from_numpy(sc32).cuda())
     keep = torch.full((1, 2, B), -1, dtype=torch.int32, device="cuda")
     fk.fk_select_keep(dev.desc, dev.scores, dev.pos, dev.len, n, B, R, keep)
-    assert np.array_equal(keep.cpu().numpy(), keep_ref)
+    gpu.assert_keep_equal(keep.cpu().numpy(), keep_ref, c.len, B)
     fk.fk_compact(dev.desc, dev.K, dev.V, dev.pos, dev.len, keep, B)
     ora.compact(c, keep_ref, B)
     h = dev.host(ora)
