@@ -428,9 +428,15 @@ def bench_stack(args, w: si.Workload):
     torch.cuda.synchronize()
     ms = sum(a.elapsed_time(b) for a, b in br)
     achieved = sum(step_bytes) / (ms * 1e-3) / 1e9
+    cfg_no = {"cfg2": 2, "cfg3": 3}.get(w.name[:4])
+    ratio = profile_value(f"attn_kernel_cfg{cfg_no}_stack.txt", "traffic_over_algorithmic") if cfg_no and args.prompt is None and args.hidden is None else None
+    avg_bytes = sum(step_bytes) / (K_steps * NL)
     result["roofline"] = {"kernel": "attn_kernel (fk_decode_step), all layers of a step between one pair of HIP events", "bound": "hbm",
-                          "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": None,
-                          "avg_launch_us": ms * 1e3 / (K_steps * NL), "algorithmic_bytes_per_launch": sum(step_bytes) / (K_steps * NL)}
+                          "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
+                          "traffic": None if ratio is None else ratio * avg_bytes,
+                          "traffic_source": None if ratio is None else f"profiles/attn_kernel_cfg{cfg_no}_stack.txt: counter bytes / algorithmic bytes of this command, times this run's algorithmic bytes",
+                          "avg_launch_us": ms * 1e3 / (K_steps * NL), "algorithmic_bytes_per_launch": avg_bytes,
+                          "working_set_mb": NL * Bt * Hkv * float(np.mean(lens[:K_steps])) * D * 2 * e / 1e6, "resident_in": "hbm"}
     print(json.dumps(result), flush=True)
 
 
@@ -616,8 +622,12 @@ def main():
     torch.cuda.synchronize()
     reset(len0)
     torch.cuda.synchronize()
+    done = torch.cuda.Event()
     t0 = time.perf_counter()
     run(K_steps, clock0, lens_at, dp)
+    done.record(stream)
+    while not done.query():   # poll instead of sleeping in the driver: the wake-up of a blocking wait costs tens of microseconds
+        pass
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
     final_len = lenc.cpu().numpy()
@@ -663,14 +673,20 @@ def main():
         attn_us = attn_ms * 1e3 / K_steps
         avg_bytes = total_attn_bytes / K_steps
         achieved = avg_bytes / (attn_us * 1e-6) / 1e9
-        ratio = profile_value("attn_kernel_cfg1_hbm_traffic.txt", "traffic_over_algorithmic") \
-            if (w.name.startswith("cfg1-qwen3-4b-layer") and steady and not args.features and args.hidden is None) else None
+        ratio, ratio_file = None, None
+        if not args.features and args.hidden is None and args.policy == "topk":
+            if w.name == "cfg1-qwen3-4b-layer" and steady:
+                ratio_file = "attn_kernel_cfg1_hbm_traffic.txt"
+            elif w.name == "cfg4-ragged-batch64" and K_steps == w.steps:
+                ratio_file = "attn_kernel_cfg4_ragged.txt"
+            if ratio_file:
+                ratio = profile_value(ratio_file, "traffic_over_algorithmic")
         result["roofline"] = {
             "kernel": "attn_kernel (fk_decode_step_feat: append + attention + attention-feature update, one launch)" if args.features
             else "attn_kernel (fk_decode_step via fk_decode_window: append + attention, one launch per step)",
             "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
             "traffic": None if ratio is None else ratio * avg_bytes,
-            "traffic_source": None if ratio is None else "profiles/attn_kernel_cfg1_hbm_traffic.txt: counter bytes / algorithmic bytes at the same steady state, times this run's algorithmic bytes",
+            "traffic_source": None if ratio is None else f"profiles/{ratio_file}: counter bytes / algorithmic bytes of the same workload, times this run's algorithmic bytes",
             "avg_launch_us": attn_us, "algorithmic_bytes_per_launch": avg_bytes,
             "working_set_mb": ws_mb,
             "resident_in": "infinity cache (the K + V of this one layer are re-read every step and fit its 256 MB)" if ws_mb < 256 else "hbm"}

@@ -23,12 +23,13 @@
  *   - descriptor structs are HOST memory, read during the call only;
  *   - all other pointers are DEVICE pointers, 16-byte aligned, owned by the caller;
  *   - `stream` is a hipStream_t passed as void* (NULL = the null stream); every call
- *     only enqueues work on it and returns; nothing is allocated, no state is kept;
+ *     only enqueues work on it and returns; nothing is allocated.  The only state the library keeps is per
+ *     device and invisible to results: flags "this kernel's dynamic-LDS limit has been raised" and, for
+ *     fk_decode_step_static, the address of its fixed scratch array;
  *   - errors are return codes; arguments are validated on the host before any launch;
  *   - `max_len` is a host-side upper bound on every len[r] at the time the kernels run
- *     (pass `capacity` when unknown); it only sizes the launch.  fk_decode_attn / fk_decode_step stay
- *     correct when a row is longer than max_len (its last split runs on to the row's end); fk_score_kv
- *     may leave slots beyond max_len unscored.
+ *     (pass `capacity` when unknown); it only sizes the launch.  Every call stays correct when a row is longer
+ *     than max_len (the last workgroup of the row runs on to the row's end: slower, same results).
  *   - supported: head_dim 64 or 128; dtype fp32 or bf16; n_q_heads a multiple of
  *     n_kv_heads with group size <= 8; capacity < 2^24.
  */

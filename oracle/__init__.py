@@ -19,7 +19,10 @@ import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "fk_oracle.c")
-_SO = os.path.join(_HERE, "libfk_oracle.so")
+# FK_ORACLE_SANITIZE=1: the same source built with AddressSanitizer + UndefinedBehaviorSanitizer into a library of its
+# own (the process must have the ASan runtime preloaded); the tests run the pins under it in a child process.
+_SANITIZE = os.environ.get("FK_ORACLE_SANITIZE", "") == "1"
+_SO = os.path.join(_HERE, "libfk_oracle_san.so" if _SANITIZE else "libfk_oracle.so")
 _lib = None
 
 F32, BF16 = 0, 1
@@ -29,7 +32,8 @@ _DT = {"f32": F32, "bf16": BF16}
 def build(force: bool = True) -> str:
     """Compile the oracle with gcc (-O2, OpenMP for the trivially parallel row loops)."""
     if force or not os.path.exists(_SO) or os.path.getmtime(_SO) < os.path.getmtime(_SRC):
-        subprocess.check_call(["gcc", "-O2", "-fopenmp", "-shared", "-fPIC", "-Wall", "-o", _SO, _SRC, "-lm"])
+        flags = ["-O1", "-g", "-fsanitize=address,undefined", "-fno-omit-frame-pointer"] if _SANITIZE else ["-O2"]
+        subprocess.check_call(["gcc", *flags, "-fopenmp", "-shared", "-fPIC", "-Wall", "-o", _SO, _SRC, "-lm"])
     return _SO
 
 

@@ -82,6 +82,28 @@ def test_decode_attn_closed_forms_on_device(gpu, ora):
     np.testing.assert_allclose(got2[0, 2], c2.V[0, 0, 217].astype(np.float64), atol=1e-5)
 
 
+def test_split_merge_many_splits_back_to_back(gpu, ora):
+    """One row cut into as many splits as the plan ever uses (128 workgroups whose records are merged by the last one to
+    arrive), 64 launches in a row on one workspace with no host synchronisation in between: every launch must find the
+    arrival counter at zero and every merge must see all records of its own launch.  Cold-cache variant too."""
+    import paper_2602_03203_amd as fk
+    D, cap, n, g, nq = 128, 20000, 19777, 4, 64
+    c = random_cache(ora, 4711, "bf16", 1, 1, cap, D, lens=[n], scale=0.5)
+    for cold in (False, True):
+        desc = fk.CacheDesc(1, g, 1, D, cap, "bf16", cold=cold)
+        dev = gpu.DevCache(c, g)
+        ws = fk.new_attn_workspace(desc)
+        qs = [random_q(9000 + i, "bf16", 1, g, D, scale=1.0 + 0.05 * i) for i in range(nq)]
+        dq = gpu.to_dev(np.stack(qs))
+        outs = torch.empty((nq, 1, g, D), dtype=torch.bfloat16, device="cuda")
+        for i in range(nq):
+            fk.fk_decode_attn(desc, dq[i], dev.K, dev.V, dev.len, n, 0.2, outs[i], ws)
+        torch.cuda.synchronize()
+        assert int(ws[:4].view(torch.int32)[0]) == 0          # the row's arrival counter is back at zero
+        for i in range(nq):
+            gpu.assert_attn_close(gpu.out_to_f64(outs[i]), ora.decode_attn(c, qs[i], 0.2), "bf16", f"launch {i} (cold={cold})")
+
+
 def test_rows_of_a_sequence_may_hold_different_counts(gpu, ora):
     """Every row carries its own length: heads of one sequence with different counts (the oracle sees
     each row as a one-head sequence)."""
@@ -158,6 +180,18 @@ def test_score_kv_matches_oracle(gpu, ora, dtype, D, H, Hkv, cap, lens, per_head
     gpu.assert_scores_close(got, ref, lens, "scores")
     for b in range(Bt):                                   # slots past len are not written
         assert np.isnan(got[b, :, lens[b]:]).all()
+    if dtype == "f32":
+        # fp32 path (plain FMA, library erf): besides the bar above, every score within 1e-5 of the sum of the
+        # magnitudes of its terms, so that an fp32 regression cannot hide under the row-scale floor of that bar
+        from scipy.special import erf
+        for b in range(Bt):
+            n = lens[b]
+            for h in range(Hkv):
+                x = np.concatenate([c.K[b, h, :n], c.V[b, h, :n]], axis=1).astype(np.float64)
+                hw = h if per_head else 0
+                z = x @ W1[hw].astype(np.float64) + b1[hw]
+                terms = np.abs(0.5 * z * (1.0 + erf(z / np.sqrt(2.0))) * W2[hw]).sum(axis=1) + abs(float(b2[hw]))
+                assert (np.abs(got[b, h, :n] - ref[b, h, :n]) <= 1e-5 * terms).all(), f"fp32 scores row ({b},{h})"
     # rows at or under skip_len (the budget, in the protocol) are left alone, the others get the same scores
     skip = sorted(lens)[len(lens) // 2]
     dev.scores.fill_(float("nan"))
