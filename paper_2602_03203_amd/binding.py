@@ -90,6 +90,46 @@ def _check(code: int, where: str) -> None:
         raise FkError(code, where)
 
 
+_recording = None  # while prepare() runs: the list that receives the library calls instead of the library
+
+
+def _call(name: str, *cargs) -> None:
+    f = getattr(lib(), name)
+    if _recording is not None:
+        _recording.append((f, cargs, name))
+        return
+    _check(f(*cargs), name)
+
+
+def prepare(fn, *args, **kwargs):
+    """Marshal once, call many times.  Runs the wrapper `fn(*args, **kwargs)` WITHOUT calling the library and returns a
+    zero-argument callable that makes the same library call(s) with the arguments as converted now (device pointers,
+    sizes, stream handle).  For loops in which Python's per-call marshalling would show in the timing.  The tensors
+    must stay alive and in place for as long as the callable is used."""
+    global _recording
+    assert _recording is None, "prepare() does not nest"
+    _recording = calls = []
+    try:
+        fn(*args, **kwargs)
+    finally:
+        _recording = None
+    if len(calls) == 1:
+        f, cargs, name = calls[0]
+
+        def run_one():
+            code = f(*cargs)
+            if code:
+                _check(code, name)
+        return run_one
+
+    def run_all():
+        for f, cargs, name in calls:
+            code = f(*cargs)
+            if code:
+                _check(code, name)
+    return run_all
+
+
 def _ptr(t) -> int:
     if t is None:
         return 0
@@ -122,8 +162,8 @@ class CacheDesc:
 
 
 def fk_append(desc: CacheDesc, K, V, pos, length, k_new, v_new, pos_new, stream=None) -> None:
-    _check(lib().fk_append(ctypes.byref(desc.c()), _ptr(K), _ptr(V), _ptr(pos), _ptr(length), _ptr(k_new),
-                           _ptr(v_new), _ptr(pos_new), _stream(stream)), "fk_append")
+    _call("fk_append", ctypes.byref(desc.c()), _ptr(K), _ptr(V), _ptr(pos), _ptr(length), _ptr(k_new),
+                           _ptr(v_new), _ptr(pos_new), _stream(stream))
 
 
 def fk_decode_attn_workspace(desc: CacheDesc, max_len: int) -> int:
@@ -138,26 +178,25 @@ def new_attn_workspace(desc: CacheDesc) -> "torch.Tensor":
 def fk_decode_attn(desc: CacheDesc, q, K, V, length, max_len: int, softmax_scale: float, out, workspace,
                    stream=None) -> None:
     nbytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
-    _check(lib().fk_decode_attn(ctypes.byref(desc.c()), _ptr(q), _ptr(K), _ptr(V), _ptr(length), int(max_len),
-                                float(softmax_scale), _ptr(out), _ptr(workspace), nbytes, _stream(stream)),
-           "fk_decode_attn")
+    _call("fk_decode_attn", ctypes.byref(desc.c()), _ptr(q), _ptr(K), _ptr(V), _ptr(length), int(max_len),
+                                float(softmax_scale), _ptr(out), _ptr(workspace), nbytes, _stream(stream))
 
 
 def fk_decode_step(desc: CacheDesc, q, K, V, pos, length, k_new, v_new, pos_new, max_len: int, softmax_scale: float,
                    out, workspace, stream=None) -> None:
     """fk_append + fk_decode_attn in one launch; max_len bounds len[b] + 1."""
     nbytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
-    _check(lib().fk_decode_step(ctypes.byref(desc.c()), _ptr(q), _ptr(K), _ptr(V), _ptr(pos), _ptr(length), _ptr(k_new),
+    _call("fk_decode_step", ctypes.byref(desc.c()), _ptr(q), _ptr(K), _ptr(V), _ptr(pos), _ptr(length), _ptr(k_new),
                                 _ptr(v_new), _ptr(pos_new), int(max_len), float(softmax_scale), _ptr(out),
-                                _ptr(workspace), nbytes, _stream(stream)), "fk_decode_step")
+                                _ptr(workspace), nbytes, _stream(stream))
 
 
 def fk_decode_step_static(desc: CacheDesc, q, K, V, pos, length, k_new, v_new, pos_new, max_len: int, softmax_scale: float,
                           out, stream=None) -> None:
     """fk_decode_step on the library's own fixed scratch: no workspace argument, nothing allocated."""
-    _check(lib().fk_decode_step_static(ctypes.byref(desc.c()), _ptr(q), _ptr(K), _ptr(V), _ptr(pos), _ptr(length), _ptr(k_new),
+    _call("fk_decode_step_static", ctypes.byref(desc.c()), _ptr(q), _ptr(K), _ptr(V), _ptr(pos), _ptr(length), _ptr(k_new),
                                        _ptr(v_new), _ptr(pos_new), int(max_len), float(softmax_scale), _ptr(out),
-                                       _stream(stream)), "fk_decode_step_static")
+                                       _stream(stream))
 
 
 def fk_decode_window(desc: CacheDesc, q_seq, K, V, pos, length, k_seq, v_seq, pos_seq, n_steps: int, max_len_first: int,
@@ -165,9 +204,9 @@ def fk_decode_window(desc: CacheDesc, q_seq, K, V, pos, length, k_seq, v_seq, po
     """n_steps consecutive decode steps enqueued by one call: step t uses q_seq[t], k_seq[t], v_seq[t], pos_seq[t]
     and writes out_seq[t]; max_len_first bounds len + 1 at the first step."""
     nbytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
-    _check(lib().fk_decode_window(ctypes.byref(desc.c()), _ptr(q_seq), _ptr(K), _ptr(V), _ptr(pos), _ptr(length), _ptr(k_seq),
+    _call("fk_decode_window", ctypes.byref(desc.c()), _ptr(q_seq), _ptr(K), _ptr(V), _ptr(pos), _ptr(length), _ptr(k_seq),
                                   _ptr(v_seq), _ptr(pos_seq), int(n_steps), int(max_len_first), float(softmax_scale),
-                                  _ptr(out_seq), _ptr(workspace), nbytes, _stream(stream)), "fk_decode_window")
+                                  _ptr(out_seq), _ptr(workspace), nbytes, _stream(stream))
 
 
 def fk_score_kv(desc: CacheDesc, K, V, length, max_len: int, W1, b1, W2, b2, scores, stream=None, skip_len: int = 0) -> None:
@@ -176,26 +215,26 @@ def fk_score_kv(desc: CacheDesc, K, V, length, max_len: int, W1, b1, W2, b2, sco
     n_sets, _, hidden = W1.shape
     sc = fk_scorer(_ptr(W1), _ptr(b1), _ptr(W2), _ptr(b2), int(hidden), 1 if n_sets == desc.n_kv_heads and n_sets > 1 else 0,
                    int(skip_len))
-    _check(lib().fk_score_kv(ctypes.byref(desc.c()), _ptr(K), _ptr(V), _ptr(length), int(max_len), ctypes.byref(sc),
-                             _ptr(scores), _stream(stream)), "fk_score_kv")
+    _call("fk_score_kv", ctypes.byref(desc.c()), _ptr(K), _ptr(V), _ptr(length), int(max_len), ctypes.byref(sc),
+                             _ptr(scores), _stream(stream))
 
 
 def fk_select_keep(desc: CacheDesc, scores, pos, length, max_len: int, budget: int, protect_recent: int, keep_idx,
                    stream=None) -> None:
-    _check(lib().fk_select_keep(ctypes.byref(desc.c()), _ptr(scores), _ptr(pos), _ptr(length), int(max_len),
-                                int(budget), int(protect_recent), _ptr(keep_idx), _stream(stream)), "fk_select_keep")
+    _call("fk_select_keep", ctypes.byref(desc.c()), _ptr(scores), _ptr(pos), _ptr(length), int(max_len),
+                                int(budget), int(protect_recent), _ptr(keep_idx), _stream(stream))
 
 
 def fk_select_keep_sampled(desc: CacheDesc, scores, noise, pos, length, max_len: int, budget: int, protect_recent: int,
                            n_candidates: int, keep_idx, stream=None) -> None:
-    _check(lib().fk_select_keep_sampled(ctypes.byref(desc.c()), _ptr(scores), _ptr(noise), _ptr(pos), _ptr(length),
+    _call("fk_select_keep_sampled", ctypes.byref(desc.c()), _ptr(scores), _ptr(noise), _ptr(pos), _ptr(length),
                                         int(max_len), int(budget), int(protect_recent), int(n_candidates),
-                                        _ptr(keep_idx), _stream(stream)), "fk_select_keep_sampled")
+                                        _ptr(keep_idx), _stream(stream))
 
 
 def fk_compact(desc: CacheDesc, K, V, pos, length, keep_idx, budget: int, stream=None) -> None:
-    _check(lib().fk_compact(ctypes.byref(desc.c()), _ptr(K), _ptr(V), _ptr(pos), _ptr(length), _ptr(keep_idx),
-                            int(budget), _stream(stream)), "fk_compact")
+    _call("fk_compact", ctypes.byref(desc.c()), _ptr(K), _ptr(V), _ptr(pos), _ptr(length), _ptr(keep_idx),
+                            int(budget), _stream(stream))
 
 
 def feat_heads(desc: CacheDesc) -> int:
@@ -216,10 +255,10 @@ def fk_decode_step_feat(desc: CacheDesc, q, K, V, pos, length, k_new, v_new, pos
                         feat, chunk_pos: int, chunk_len: int, out, workspace, stream=None) -> None:
     """fk_decode_step that also accounts the step's attention weights in the feature state."""
     nbytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
-    _check(lib().fk_decode_step_feat(ctypes.byref(desc.c()), _ptr(q), _ptr(K), _ptr(V), _ptr(pos), _ptr(length),
+    _call("fk_decode_step_feat", ctypes.byref(desc.c()), _ptr(q), _ptr(K), _ptr(V), _ptr(pos), _ptr(length),
                                      _ptr(k_new), _ptr(v_new), _ptr(pos_new), int(max_len), float(softmax_scale),
                                      _ptr(feat), int(chunk_pos), int(chunk_len), _ptr(out), _ptr(workspace), nbytes,
-                                     _stream(stream)), "fk_decode_step_feat")
+                                     _stream(stream))
 
 
 def fk_score_kv_feat(desc: CacheDesc, K, V, feat, length, max_len: int, W1, b1, W2, b2, scores, stream=None,
@@ -228,13 +267,13 @@ def fk_score_kv_feat(desc: CacheDesc, K, V, feat, length, max_len: int, W1, b1, 
     n_sets, _, hidden = W1.shape
     sc = fk_scorer(_ptr(W1), _ptr(b1), _ptr(W2), _ptr(b2), int(hidden), 1 if n_sets == desc.n_kv_heads and n_sets > 1 else 0,
                    int(skip_len))
-    _check(lib().fk_score_kv_feat(ctypes.byref(desc.c()), _ptr(K), _ptr(V), _ptr(feat), _ptr(length), int(max_len),
-                                  ctypes.byref(sc), _ptr(scores), _stream(stream)), "fk_score_kv_feat")
+    _call("fk_score_kv_feat", ctypes.byref(desc.c()), _ptr(K), _ptr(V), _ptr(feat), _ptr(length), int(max_len),
+                                  ctypes.byref(sc), _ptr(scores), _stream(stream))
 
 
 def fk_compact_feat(desc: CacheDesc, K, V, pos, feat, length, keep_idx, budget: int, stream=None) -> None:
-    _check(lib().fk_compact_feat(ctypes.byref(desc.c()), _ptr(K), _ptr(V), _ptr(pos), _ptr(feat), _ptr(length),
-                                 _ptr(keep_idx), int(budget), _stream(stream)), "fk_compact_feat")
+    _call("fk_compact_feat", ctypes.byref(desc.c()), _ptr(K), _ptr(V), _ptr(pos), _ptr(feat), _ptr(length),
+                                 _ptr(keep_idx), int(budget), _stream(stream))
 
 
 def fk_golden_steps(T: int, budget: int, interval: int) -> int:
@@ -243,17 +282,17 @@ def fk_golden_steps(T: int, budget: int, interval: int) -> int:
 
 def fk_golden_scores(A, n_kv_heads: int, T: int, budget: int, interval: int, block_scores, alpha, stream=None) -> None:
     """A [n_q_heads, T, ld] fp32 or bf16 (ld = A.shape[2] >= T); block_scores, alpha [n_kv_heads, M, T] fp32."""
-    _check(lib().fk_golden_scores(_ptr(A), FK_F32 if A.dtype == torch.float32 else FK_BF16, int(A.shape[0]), int(n_kv_heads),
+    _call("fk_golden_scores", _ptr(A), FK_F32 if A.dtype == torch.float32 else FK_BF16, int(A.shape[0]), int(n_kv_heads),
                                   int(T), int(A.shape[2]), int(budget), int(interval), _ptr(block_scores), _ptr(alpha),
-                                  _stream(stream)), "fk_golden_scores")
+                                  _stream(stream))
 
 
 def fk_golden_trace(alpha, T: int, budget: int, interval: int, kept, stream=None) -> None:
     """alpha [n_kv_heads, M, T] fp32; kept [n_kv_heads, M, budget] int32."""
-    _check(lib().fk_golden_trace(_ptr(alpha), int(alpha.shape[0]), int(T), int(budget), int(interval), _ptr(kept),
-                                 _stream(stream)), "fk_golden_trace")
+    _call("fk_golden_trace", _ptr(alpha), int(alpha.shape[0]), int(T), int(budget), int(interval), _ptr(kept),
+                                 _stream(stream))
 
 
 def fk_stream_read(src, sink, stream=None) -> None:
     """Measurement helper: stream-read the whole tensor `src` once (sink: >= 4 bytes of device memory)."""
-    _check(lib().fk_stream_read(_ptr(src), src.numel() * src.element_size(), _ptr(sink), _stream(stream)), "fk_stream_read")
+    _call("fk_stream_read", _ptr(src), src.numel() * src.element_size(), _ptr(sink), _stream(stream))
