@@ -232,6 +232,27 @@ def test_select_keep_bit_exact(gpu, ora, Bt, Hkv, cap, lens, budget, recent, tie
     gpu.assert_keep_equal(keep.cpu().numpy(), ref, ln, budget)
 
 
+def test_prepared_call_replays_the_direct_call(gpu, ora):
+    """fk.prepare marshals once; the callable it returns makes the same library call each time it is used."""
+    import paper_2602_03203_amd as fk
+    Bt, Hkv, cap, budget, recent = 2, 4, 2176, 2048, 128
+    sc = si.gen_scores(777, (Bt, Hkv, cap), ties=3)
+    ln = np.array([cap, 2100], np.int32)
+    ref = ora.select_keep(sc, np.tile(np.arange(cap, dtype=np.int32), (Bt, Hkv, 1)), ln, budget, recent, "sort")
+    desc = fk.CacheDesc(Bt, Hkv, Hkv, 128, cap, "bf16")
+    d_sc, d_ln = gpu.to_dev(sc), gpu.to_dev(np.repeat(ln[:, None], Hkv, 1))
+    keep = torch.full((Bt, Hkv, budget), -1, dtype=torch.int32, device="cuda")
+    call = fk.prepare(fk.fk_select_keep, desc, d_sc, None, d_ln, cap, budget, recent, keep)
+    torch.cuda.synchronize()
+    assert (keep == -1).all()                      # preparing calls nothing
+    for _ in range(2):
+        keep.fill_(-1)
+        call()
+        gpu.assert_keep_equal(keep.cpu().numpy(), ref, ln, budget)
+    with pytest.raises(fk.FkError):                # an error status still raises, when prepared and when replayed
+        fk.prepare(fk.fk_select_keep, desc, d_sc, None, d_ln, cap, cap + 1, recent, keep)()
+
+
 def test_select_keep_special_values(gpu, ora):
     import paper_2602_03203_amd as fk
     cap, budget, recent = 1200, 700, 100
