@@ -75,34 +75,13 @@ template <int D, int GF> struct ScoreCfg {
 
 __device__ __forceinline__ uint32_t bf16_rn(float x) { return (__float_as_uint(x) + 0x7fffu + ((__float_as_uint(x) >> 16) & 1u)) >> 16; }
 
-// LDS: Wt [H][FS] bf16 | b1 [H] f32 | w2 [H] f32
-template <int D, int NT, int GF>
-__global__ __launch_bounds__(kScoreThreads) void score_mfma_kernel(
-    const bf16_t* __restrict__ K, const bf16_t* __restrict__ V, const float* __restrict__ feat,
-    const int32_t* __restrict__ len,
-    const bf16_t* __restrict__ W1, const float* __restrict__ b1, const float* __restrict__ W2,
-    const float* __restrict__ b2, int H, int per_head, int skip_len, int n_kv, int cap, int pairs_per_block,
-    float* __restrict__ scores) {
+// LDS of the MFMA kernels: Wt [HP][FS] bf16 | b1 [HP] f32 | w2 [HP] f32
+template <int D, int GF>
+__device__ __forceinline__ void stage_w1t(const bf16_t* __restrict__ W1, const float* __restrict__ b1, const float* __restrict__ W2,
+                                          int hw, int H, int HP, bf16_t* s_wt, float* s_b1, float* s_w2) {
     using SC = ScoreCfg<D, GF>;
     constexpr int F = SC::F;
-    constexpr int FS = SC::FS;     // LDS row stride in bf16 elements
-    constexpr int KS = 2 * D / 16; // k-steps of 16 features over k and v
-    constexpr int KA = SC::KA;
-    const int row = blockIdx.y;
-    const int hkv = row % n_kv;
-    const int n = min(len[row], cap);
-    const int p_begin = blockIdx.x * pairs_per_block;
-    if (p_begin >= n || n <= skip_len) return;
-    // the last workgroup of a row runs on to the row's end (a max_len hint below len[row] costs time, not scores)
-    const int p_end = blockIdx.x == gridDim.x - 1 ? n : min(p_begin + pairs_per_block, n);
-    const int hw = per_head ? hkv : 0;
-
-    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-    bf16_t* s_wt = reinterpret_cast<bf16_t*>(smem);
-    const int HP = (H + 31) / 32 * 32;  // hidden units padded to whole MFMA tiles: zero weights, zero W2
-    float* s_b1 = reinterpret_cast<float*>(smem + (size_t)HP * FS * sizeof(bf16_t));
-    float* s_w2 = s_b1 + HP;
-
+    constexpr int FS = SC::FS;
     // stage W1^T: a thread takes two consecutive features f, f+1 and 8 consecutive hidden
     // units, and writes 8 dwords (W1[f][j], W1[f+1][j]) to Wt[j][f..f+1].  Four consecutive lanes take four
     // consecutive 16-byte chunks of the same two W1 rows (64 contiguous bytes per row: one request to the memory
@@ -141,6 +120,36 @@ __global__ __launch_bounds__(kScoreThreads) void score_mfma_kernel(
             s_w2[j] = j < H ? W2[(size_t)hw * H + j] : 0.f;
         }
     }
+}
+
+// LDS: Wt [H][FS] bf16 | b1 [H] f32 | w2 [H] f32
+template <int D, int NT, int GF>
+__global__ __launch_bounds__(kScoreThreads) void score_mfma_kernel(
+    const bf16_t* __restrict__ K, const bf16_t* __restrict__ V, const float* __restrict__ feat,
+    const int32_t* __restrict__ len,
+    const bf16_t* __restrict__ W1, const float* __restrict__ b1, const float* __restrict__ W2,
+    const float* __restrict__ b2, int H, int per_head, int skip_len, int n_kv, int cap, int pairs_per_block,
+    float* __restrict__ scores) {
+    using SC = ScoreCfg<D, GF>;
+    constexpr int FS = SC::FS;     // LDS row stride in bf16 elements
+    constexpr int KS = 2 * D / 16; // k-steps of 16 features over k and v
+    constexpr int KA = SC::KA;
+    const int row = blockIdx.y;
+    const int hkv = row % n_kv;
+    const int n = min(len[row], cap);
+    const int p_begin = blockIdx.x * pairs_per_block;
+    if (p_begin >= n || n <= skip_len) return;
+    // the last workgroup of a row runs on to the row's end (a max_len hint below len[row] costs time, not scores)
+    const int p_end = blockIdx.x == gridDim.x - 1 ? n : min(p_begin + pairs_per_block, n);
+    const int hw = per_head ? hkv : 0;
+
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    bf16_t* s_wt = reinterpret_cast<bf16_t*>(smem);
+    const int HP = (H + 31) / 32 * 32;  // hidden units padded to whole MFMA tiles: zero weights, zero W2
+    float* s_b1 = reinterpret_cast<float*>(smem + (size_t)HP * FS * sizeof(bf16_t));
+    float* s_w2 = s_b1 + HP;
+
+    stage_w1t<D, GF>(W1, b1, W2, hw, H, HP, s_wt, s_b1, s_w2);
     __syncthreads();
 
     const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
