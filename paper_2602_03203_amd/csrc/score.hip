@@ -23,16 +23,10 @@ namespace fk {
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
 typedef __attribute__((ext_vector_type(16))) float f32x16_t;
 
-#ifndef FK_SCORE_NT
-#define FK_SCORE_NT 1
-#endif
-#ifndef FK_SCORE_THREADS
-#define FK_SCORE_THREADS 1024
-#endif
-// NT pair tiles share every LDS read of a W1^T operand; several wavefronts per SIMD so that the MFMAs of one
-// overlap the gelu of the others
-static constexpr int kScoreNT = FK_SCORE_NT;
-static constexpr int kScoreThreads = FK_SCORE_THREADS;
+// NT pair tiles of a wavefront share every LDS read of a W1^T operand (1: with two, only 8 wavefronts fit the
+// registers and the kernel is slower); 16 wavefronts per workgroup, the most the pair operands leave registers for
+static constexpr int kScoreNT = 1;
+static constexpr int kScoreThreads = 1024;
 static constexpr int kScoreWaves = kScoreThreads / kWave;
 static constexpr int kWPad = 8;  // bf16 elements of padding per transposed W1 row in LDS
 
