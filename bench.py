@@ -281,6 +281,7 @@ def bench_oneshot(args):
         K0, V0, pos0 = K[:, :, :B].clone(), V[:, :, :B].clone(), pos[:, :, :B].clone()
         scores = torch.zeros((Bt, Hkv, n), dtype=torch.float32, device="cuda")
         keep = torch.zeros((Bt, Hkv, B), dtype=torch.int32, device="cuda")
+        sel_ws = torch.empty(max(fk.fk_select_keep_workspace(desc, n, B, R), 16), dtype=torch.uint8, device="cuda")
         us = np.zeros(3)
         wall = 0.0
         for it in range(W_steps + K_steps):
@@ -291,7 +292,7 @@ def bench_oneshot(args):
             ev[0].record(stream)
             fk.fk_score_kv(desc, K, V, ln, n, W1, b1, W2, b2, scores, stream, skip_len=B)
             ev[1].record(stream)
-            fk.fk_select_keep(desc, scores, pos, ln, n, B, R, keep, stream)
+            fk.fk_select_keep_ws(desc, scores, pos, ln, n, B, R, keep, sel_ws, stream)
             ev[2].record(stream)
             fk.fk_compact(desc, K, V, pos, ln, keep, B, stream)
             ev[3].record(stream)

@@ -184,6 +184,23 @@ fk_status fk_select_keep(const fk_cache_desc *desc, const float *scores, const i
                          int32_t protect_recent, int32_t *keep_idx, void *stream);
 
 /*
+ * fk_select_keep for few, long rows (Section 4.3: one-shot compression of a long prompt before
+ * decoding; the same selection rule, applied once to rows far over budget).  Same arguments,
+ * same result bit for bit.  With at most 64 rows of max_len >= 16384 a row is cut into chunks that
+ * are selected by one workgroup each, and a second launch selects among the chunks' survivors (a
+ * pair among the row's best budget - protect_recent is among its chunk's best under the same total
+ * order); otherwise this is fk_select_keep.  workspace: caller-owned device scratch of at least
+ * fk_select_keep_workspace(desc, max_len, budget, protect_recent) bytes (0 when rows are not split;
+ * then workspace may be NULL), contents undefined before and after; FK_ERR_WORKSPACE if too small.
+ */
+size_t fk_select_keep_workspace(const fk_cache_desc *desc, int32_t max_len, int32_t budget,
+                                int32_t protect_recent);
+fk_status fk_select_keep_ws(const fk_cache_desc *desc, const float *scores, const int32_t *pos,
+                            const int32_t *len, int32_t max_len, int32_t budget,
+                            int32_t protect_recent, int32_t *keep_idx, void *workspace,
+                            size_t workspace_bytes, void *stream);
+
+/*
  * Section 3.1 Eq. 2 and Appendix B.2 (Top-K multinomial eviction, the paper's inference policy).
  * For every row with len[r] > budget, E = len[r] - budget pairs go: the last `protect_recent` live
  * slots are kept; of the others, the max(n_candidates, E) lowest-ranked under (score descending,

@@ -20,7 +20,7 @@ FK_OK, FK_ERR_INVALID_ARG, FK_ERR_UNSUPPORTED, FK_ERR_WORKSPACE, FK_ERR_LAUNCH =
 FK_F32, FK_BF16 = 0, 1
 
 SYMBOLS = ["fk_status_string", "fk_version", "fk_append", "fk_decode_attn_workspace", "fk_decode_attn", "fk_decode_step", "fk_decode_window", "fk_decode_step_static",
-           "fk_score_kv", "fk_select_keep", "fk_select_keep_sampled", "fk_compact", "fk_decode_step_feat_workspace",
+           "fk_score_kv", "fk_select_keep", "fk_select_keep_workspace", "fk_select_keep_ws", "fk_select_keep_sampled", "fk_compact", "fk_decode_step_feat_workspace",
            "fk_decode_step_feat", "fk_score_kv_feat", "fk_compact_feat", "fk_golden_steps", "fk_golden_scores",
            "fk_golden_trace", "fk_stream_read"]
 
@@ -63,6 +63,8 @@ def lib() -> ctypes.CDLL:
         L.fk_decode_step_static.restype, L.fk_decode_step_static.argtypes = ctypes.c_int, [dp, vp, vp, vp, vp, vp, vp, vp, vp, i32, f32, vp, vp]
         L.fk_score_kv.restype, L.fk_score_kv.argtypes = ctypes.c_int, [dp, vp, vp, vp, i32, sp, vp, vp]
         L.fk_select_keep.restype, L.fk_select_keep.argtypes = ctypes.c_int, [dp, vp, vp, vp, i32, i32, i32, vp, vp]
+        L.fk_select_keep_workspace.restype, L.fk_select_keep_workspace.argtypes = sz, [dp, i32, i32, i32]
+        L.fk_select_keep_ws.restype, L.fk_select_keep_ws.argtypes = ctypes.c_int, [dp, vp, vp, vp, i32, i32, i32, vp, vp, sz, vp]
         L.fk_select_keep_sampled.restype, L.fk_select_keep_sampled.argtypes = ctypes.c_int, [dp, vp, vp, vp, vp, i32, i32, i32, i32, vp, vp]
         L.fk_compact.restype, L.fk_compact.argtypes = ctypes.c_int, [dp, vp, vp, vp, vp, vp, i32, vp]
         L.fk_decode_step_feat_workspace.restype, L.fk_decode_step_feat_workspace.argtypes = sz, [dp]
@@ -223,6 +225,19 @@ def fk_select_keep(desc: CacheDesc, scores, pos, length, max_len: int, budget: i
                    stream=None) -> None:
     _call("fk_select_keep", ctypes.byref(desc.c()), _ptr(scores), _ptr(pos), _ptr(length), int(max_len),
                                 int(budget), int(protect_recent), _ptr(keep_idx), _stream(stream))
+
+
+def fk_select_keep_workspace(desc: CacheDesc, max_len: int, budget: int, protect_recent: int) -> int:
+    return int(lib().fk_select_keep_workspace(ctypes.byref(desc.c()), int(max_len), int(budget), int(protect_recent)))
+
+
+def fk_select_keep_ws(desc: CacheDesc, scores, pos, length, max_len: int, budget: int, protect_recent: int, keep_idx,
+                      workspace, stream=None) -> None:
+    """fk_select_keep that may split few, long rows over several workgroups; workspace: a device byte tensor of at least
+    fk_select_keep_workspace(...) bytes, or None when that is 0."""
+    nbytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _call("fk_select_keep_ws", ctypes.byref(desc.c()), _ptr(scores), _ptr(pos), _ptr(length), int(max_len), int(budget),
+          int(protect_recent), _ptr(keep_idx), _ptr(workspace), nbytes, _stream(stream))
 
 
 def fk_select_keep_sampled(desc: CacheDesc, scores, noise, pos, length, max_len: int, budget: int, protect_recent: int,

@@ -17,34 +17,89 @@ namespace fk {
 static constexpr int kSelMaxLdsKeys = 36 * 1024;  // 144 KB of keys beside the histograms
 // (Four wavefronts per row instead of sixteen were measured and dropped: 11.3 against 8.1 us; the passes are bound by
 // the latency of the key -> atomic -> barrier -> scan chain, not by instruction issue.)
-template <int THREADS>
+//
+// Long rows of a small batch (one-shot compression of a long prompt: 32 rows of 131072 pairs) would leave most of the
+// chip idle with one workgroup per row, and their keys do not fit LDS.  fk_select_keep_ws splits such rows (two launches,
+// a workspace between them): kSelChunk workgroups, one per chunk of a row, each keep the k best candidates of
+// their chunk (any pair among the row's k best is among its chunk's k best, under the same total order); kSelMerge
+// workgroups, one per row, then select among the chunks' survivors, whose keys fit LDS.  Same result, bit for bit.
+enum { kSelWhole = 0, kSelChunk = 1, kSelMerge = 2 };
+struct SelSplit {
+    int nchunk;      // chunks per row
+    int chunk_len;   // candidates per chunk (the last chunk runs on to the row's end)
+    int32_t* count;  // [rows][nchunk] survivors of every chunk
+    int32_t* cand;   // [rows][nchunk][budget - recent] their slots, ascending
+};
+
+template <int THREADS, int MODE>
 __global__ __launch_bounds__(THREADS) void select_keep_kernel(const float* __restrict__ scores,
                                                               const int32_t* __restrict__ len,
                                                               int cap, int budget, int recent, int lds_keys,
-                                                              int32_t* __restrict__ keep) {
-    const int row = blockIdx.x;
+                                                              int32_t* __restrict__ keep, SelSplit sp) {
+    const int row = MODE == kSelChunk ? blockIdx.x / sp.nchunk : blockIdx.x;
+    const int chunk = MODE == kSelChunk ? blockIdx.x % sp.nchunk : 0;
     const int n = min(len[row], cap);
-    int32_t* out = keep + (size_t)row * budget;
+    const int kmax = budget - recent;
+    int32_t* out = MODE == kSelChunk ? sp.cand + ((size_t)row * sp.nchunk + chunk) * kmax : keep + (size_t)row * budget;
     if (n <= budget) {  // nothing to prune: the identity over the whole row, which makes the compaction a no-op
-        for (int j = threadIdx.x; j < budget; j += THREADS) out[j] = j;
+        if (MODE != kSelChunk)
+            for (int j = threadIdx.x; j < budget; j += THREADS) out[j] = j;
         return;
     }
     const float* sc = scores + (size_t)row * cap;
-    const int ncand = n - recent;   // candidates: slots [0, ncand)
-    const int k = budget - recent;  // how many of them stay (0 <= k < ncand)
+    const int first = MODE == kSelChunk ? chunk * sp.chunk_len : 0;  // first slot of this workgroup's candidates
+    int ncand = n - recent;  // candidates: slots [first, first + ncand)
+    int k = kmax;            // how many of them stay (0 <= k < ncand; a chunk: k <= ncand)
 
     extern __shared__ __attribute__((aligned(16))) uint32_t s_sel_mem[];
     uint32_t* s_hist = s_sel_mem;                 // [4][256]
     uint32_t* s_wtot = s_hist + 4 * 256;          // [16][2]: kept counts of every wavefront (greater, equal)
     uint32_t* s_key = s_wtot + 32;                // [lds_keys]
+    uint32_t* s_slot = s_key + lds_keys;          // kSelMerge: [lds_keys] the candidates' slots
     constexpr int WAVES = THREADS / kWave;
     const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
+    if constexpr (MODE == kSelChunk) {
+        ncand = chunk == sp.nchunk - 1 ? ncand - first : min(ncand - first, sp.chunk_len);
+        if (ncand < 0) ncand = 0;
+        k = min(kmax, ncand);
+        if (threadIdx.x == 0) sp.count[(size_t)row * sp.nchunk + chunk] = k;
+        if (k == ncand) {  // the whole chunk survives (also: an empty chunk, nothing to keep)
+            for (int j = threadIdx.x; j < ncand; j += THREADS) out[j] = first + j;
+            return;
+        }
+        sc += first;
+    }
+    constexpr int kMaxChunks = 16;
+    int base_of[kMaxChunks + 1];  // kSelMerge: where every chunk's survivors start in the merged list (registers)
+    if constexpr (MODE == kSelMerge) {
+        int tot = 0;
+#pragma unroll
+        for (int c = 0; c < kMaxChunks; ++c) {
+            base_of[c] = tot;
+            if (c < sp.nchunk) tot += sp.count[(size_t)row * sp.nchunk + c];
+        }
+        base_of[kMaxChunks] = tot;
+        ncand = tot;  // >= k: every chunk keeps min(k, its size)
+    }
 
     // The row's keys are read from global memory once and kept in LDS (rows beyond the LDS share of the launch are
     // re-read from global memory in every pass).  Eight loads in flight per thread.
-    const bool in_lds = ncand <= lds_keys;
+    const bool in_lds = ncand <= lds_keys;  // kSelMerge: the host sized the launch so that it is
     for (int i = threadIdx.x; i < 4 * 256; i += THREADS) s_hist[i] = 0;
-    if (in_lds) {
+    if constexpr (MODE == kSelMerge) {
+#pragma unroll
+        for (int c = 0; c < kMaxChunks; ++c) {
+            if (c < sp.nchunk) {
+                const int32_t* list = sp.cand + ((size_t)row * sp.nchunk + c) * kmax;
+                const int cnt = base_of[c + 1] - base_of[c];
+                for (int o = threadIdx.x; o < cnt; o += THREADS) {
+                    const int slot = list[o];
+                    s_slot[base_of[c] + o] = (uint32_t)slot;
+                    s_key[base_of[c] + o] = score_key(sc[slot]);
+                }
+            }
+        }
+    } else if (in_lds) {
         for (int i0 = threadIdx.x; i0 < ncand; i0 += 8 * THREADS) {
             float v[8];
 #pragma unroll
@@ -143,8 +198,9 @@ __global__ __launch_bounds__(THREADS) void select_keep_kernel(const float* __res
                     const uint32_t g_below = __builtin_amdgcn_mbcnt_hi((uint32_t)(mg >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)mg, 0));
                     const uint32_t e_below = __builtin_amdgcn_mbcnt_hi((uint32_t)(me >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)me, 0));
                     const uint32_t gb = gt_run + g_below, eb = eq_run + e_below;   // kept counts before slot i
-                    if (live && kv[u] > T) out[gb + min(eb, want)] = i;
-                    else if (live && kv[u] == T && eb < want) out[gb + eb] = i;
+                    const int slot = MODE == kSelMerge ? (live ? (int)s_slot[i] : 0) : first + i;
+                    if (live && kv[u] > T) out[gb + min(eb, want)] = slot;
+                    else if (live && kv[u] == T && eb < want) out[gb + eb] = slot;
                 }
                 gt_run += (uint32_t)__popcll(mg);
                 eq_run += (uint32_t)__popcll(me);
@@ -172,7 +228,8 @@ __global__ __launch_bounds__(THREADS) void select_keep_kernel(const float* __res
         if (in_lds) walk(few, std::true_type{}, gt_before, eq_before);
         else walk(many, std::true_type{}, gt_before, eq_before);
     }
-    for (int j = threadIdx.x; j < recent; j += THREADS) out[k + j] = ncand + j;
+    if (MODE != kSelChunk)
+        for (int j = threadIdx.x; j < recent; j += THREADS) out[k + j] = n - recent + j;
 }
 
 // ---------------------------------------------------------------------------------------
@@ -278,25 +335,101 @@ __global__ __launch_bounds__(kSelThreads) void select_keep_sampled_kernel(const 
 
 using namespace fk;
 
-extern "C" fk_status fk_select_keep(const fk_cache_desc* desc, const float* scores, const int32_t* pos,
-                                    const int32_t* len, int32_t max_len, int32_t budget,
-                                    int32_t protect_recent, int32_t* keep_idx, void* stream) {
-    (void)pos;  // slot order stands for position order (cache precondition)
+static fk_status select_check(const fk_cache_desc* desc, const float* scores, const int32_t* len, int32_t max_len,
+                              int32_t budget, int32_t protect_recent, const int32_t* keep_idx) {
     fk_status s = check_desc(desc);
     if (s != FK_OK) return s;
     if (!scores || !len || !keep_idx) return FK_ERR_INVALID_ARG;
     if (max_len <= 0 || max_len > desc->capacity) return FK_ERR_INVALID_ARG;
     if (budget <= 0 || budget > desc->capacity || protect_recent < 0 || protect_recent > budget)
         return FK_ERR_INVALID_ARG;
+    return FK_OK;
+}
+
+static fk_status select_whole(const fk_cache_desc* desc, const float* scores, const int32_t* len, int32_t max_len,
+                              int32_t budget, int32_t protect_recent, int32_t* keep_idx, hipStream_t st) {
     const int rows = desc->batch * desc->n_kv_heads;
     // LDS share for the keys: rows up to max_len keys (the hint) live in LDS; longer ones are read from global memory
     const int lds_keys = ((max_len < kSelMaxLdsKeys ? max_len : kSelMaxLdsKeys) + 3) & ~3;
     const size_t lds = sizeof(uint32_t) * (4 * 256 + 32 + (size_t)lds_keys);
-    hipStream_t st = (hipStream_t)stream;
+    auto kern = select_keep_kernel<kSelThreads, kSelWhole>;
     static bool lds_ok[kMaxDevices] = {};
-    if (!allow_dynamic_lds((const void*)select_keep_kernel<kSelThreads>, 160 * 1024, lds_ok)) return FK_ERR_LAUNCH;
-    hipLaunchKernelGGL(select_keep_kernel<kSelThreads>, dim3(rows), dim3(kSelThreads), lds, st, scores, len, desc->capacity,
-                       budget, protect_recent, lds_keys, keep_idx);
+    if (!allow_dynamic_lds((const void*)kern, 160 * 1024, lds_ok)) return FK_ERR_LAUNCH;
+    hipLaunchKernelGGL(kern, dim3(rows), dim3(kSelThreads), lds, st, scores, len, desc->capacity, budget, protect_recent,
+                       lds_keys, keep_idx, SelSplit{});
+    return launch_status();
+}
+
+extern "C" fk_status fk_select_keep(const fk_cache_desc* desc, const float* scores, const int32_t* pos,
+                                    const int32_t* len, int32_t max_len, int32_t budget,
+                                    int32_t protect_recent, int32_t* keep_idx, void* stream) {
+    (void)pos;  // slot order stands for position order (cache precondition)
+    const fk_status s = select_check(desc, scores, len, max_len, budget, protect_recent, keep_idx);
+    if (s != FK_OK) return s;
+    return select_whole(desc, scores, len, max_len, budget, protect_recent, keep_idx, (hipStream_t)stream);
+}
+
+// Rows are split when one workgroup per row would leave most CUs idle and the rows are long enough to pay for a
+// second launch; the survivors of all chunks (keys and slots) must fit the merge workgroup's LDS.
+struct SelPlan {
+    int nchunk, chunk_len;
+    size_t count_bytes, bytes;
+};
+static SelPlan select_plan(const fk_cache_desc* d, int max_len, int budget, int recent) {
+    SelPlan p = {1, 0, 0, 0};
+    const int rows = d->batch * d->n_kv_heads, kmax = budget - recent;
+    if (rows > 64 || max_len < 16384 || kmax <= 0) return p;
+    int nchunk = 256 / rows;                                   // about one workgroup per CU
+    const int fit = (kSelMaxLdsKeys / 2) / kmax;               // survivors of all chunks: keys + slots in LDS
+    if (nchunk > fit) nchunk = fit;
+    if (nchunk > 16) nchunk = 16;  // kMaxChunks of the kernel
+    if (nchunk < 2) return p;
+    p.nchunk = nchunk;
+    p.chunk_len = ((max_len - recent + nchunk - 1) / nchunk + 3) & ~3;
+    p.count_bytes = ((size_t)rows * nchunk * sizeof(int32_t) + 255) & ~(size_t)255;
+    p.bytes = p.count_bytes + (size_t)rows * nchunk * kmax * sizeof(int32_t);
+    return p;
+}
+
+extern "C" size_t fk_select_keep_workspace(const fk_cache_desc* desc, int32_t max_len, int32_t budget, int32_t protect_recent) {
+    if (check_desc(desc) != FK_OK || max_len <= 0 || max_len > desc->capacity || budget <= 0 || budget > desc->capacity ||
+        protect_recent < 0 || protect_recent > budget)
+        return 0;
+    return select_plan(desc, max_len, budget, protect_recent).bytes;
+}
+
+extern "C" fk_status fk_select_keep_ws(const fk_cache_desc* desc, const float* scores, const int32_t* pos,
+                                       const int32_t* len, int32_t max_len, int32_t budget, int32_t protect_recent,
+                                       int32_t* keep_idx, void* workspace, size_t workspace_bytes, void* stream) {
+    (void)pos;
+    const fk_status s = select_check(desc, scores, len, max_len, budget, protect_recent, keep_idx);
+    if (s != FK_OK) return s;
+    hipStream_t st = (hipStream_t)stream;
+    const SelPlan p = select_plan(desc, max_len, budget, protect_recent);
+    if (p.nchunk < 2) return select_whole(desc, scores, len, max_len, budget, protect_recent, keep_idx, st);
+    if (!workspace || workspace_bytes < p.bytes) return FK_ERR_WORKSPACE;
+    const int rows = desc->batch * desc->n_kv_heads, kmax = budget - protect_recent;
+    SelSplit sp = {p.nchunk, p.chunk_len, reinterpret_cast<int32_t*>(workspace),
+                   reinterpret_cast<int32_t*>(static_cast<char*>(workspace) + p.count_bytes)};
+    {
+        auto kern = select_keep_kernel<kSelThreads, kSelChunk>;
+        const int lds_keys = ((p.chunk_len < kSelMaxLdsKeys ? p.chunk_len : kSelMaxLdsKeys) + 3) & ~3;
+        const size_t lds = sizeof(uint32_t) * (4 * 256 + 32 + (size_t)lds_keys);
+        static bool lds_ok[kMaxDevices] = {};
+        if (!allow_dynamic_lds((const void*)kern, 160 * 1024, lds_ok)) return FK_ERR_LAUNCH;
+        hipLaunchKernelGGL(kern, dim3(rows * p.nchunk), dim3(kSelThreads), lds, st, scores, len, desc->capacity, budget,
+                           protect_recent, lds_keys, keep_idx, sp);
+        if (launch_status() != FK_OK) return FK_ERR_LAUNCH;
+    }
+    {
+        auto kern = select_keep_kernel<kSelThreads, kSelMerge>;
+        const int lds_keys = (p.nchunk * kmax + 3) & ~3;  // <= kSelMaxLdsKeys / 2 by the plan
+        const size_t lds = sizeof(uint32_t) * (4 * 256 + 32 + 2 * (size_t)lds_keys);
+        static bool lds_ok[kMaxDevices] = {};
+        if (!allow_dynamic_lds((const void*)kern, 160 * 1024, lds_ok)) return FK_ERR_LAUNCH;
+        hipLaunchKernelGGL(kern, dim3(rows), dim3(kSelThreads), lds, st, scores, len, desc->capacity, budget, protect_recent,
+                           lds_keys, keep_idx, sp);
+    }
     return launch_status();
 }
 

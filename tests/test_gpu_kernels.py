@@ -232,6 +232,56 @@ def test_select_keep_bit_exact(gpu, ora, Bt, Hkv, cap, lens, budget, recent, tie
     gpu.assert_keep_equal(keep.cpu().numpy(), ref, ln, budget)
 
 
+SPLIT_SELECT_CASES = [
+    # Bt, Hkv, cap, lens, max_len hint, budget, recent, ties -- few long rows: fk_select_keep_ws cuts them into chunks
+    (1, 4, 131072, [131072], 131072, 2048, 128, 0),            # the one-shot benchmark's row: 9 chunks
+    (2, 2, 40000, [40000, 33000], 40000, 8192, 128, 0),         # large budget: two chunks is all that fits the merge
+    (2, 2, 70000, [70000, 20011], 70000, 2048, 0, 5),           # ragged, heavy ties, nothing protected
+    (3, 1, 50000, [50000, 1500, 17000], 50000, 1600, 64, 3),    # a row under budget, a row inside the first chunks
+    (1, 2, 65536, [65536], 65536, 1, 0, 2),                     # budget 1: sixteen chunks
+    (2, 1, 90000, [90000, 88000], 20000, 4096, 4096, 0),        # everything kept is protected; hint far below the lengths
+    (1, 2, 90000, [90000], 30000, 3000, 100, 4),                # hint below the length: the last chunk runs on
+]
+
+
+@pytest.mark.parametrize("Bt,Hkv,cap,lens,hint,budget,recent,ties", SPLIT_SELECT_CASES)
+def test_select_keep_split_rows_bit_exact(gpu, ora, Bt, Hkv, cap, lens, hint, budget, recent, ties):
+    import paper_2602_03203_amd as fk
+    print(f"split select case Bt={Bt} Hkv={Hkv} cap={cap} lens={lens} hint={hint} B={budget} R={recent} ties={ties}", flush=True)
+    sc = si.gen_scores(9000 + cap + ties, (Bt, Hkv, cap), ties=ties)
+    pos = np.tile(np.arange(cap, dtype=np.int32), (Bt, Hkv, 1))
+    ln = np.asarray(lens, np.int32)
+    ref = ora.select_keep(sc, pos, ln, budget, recent, "sort")
+    desc = fk.CacheDesc(Bt, Hkv, Hkv, 128, cap, "bf16")
+    nbytes = fk.fk_select_keep_workspace(desc, hint, budget, recent)
+    assert (nbytes > 0) == (budget > recent)       # these shapes are split unless nothing is selected
+    ws = torch.full((max(nbytes, 16),), 0xA5, dtype=torch.uint8, device="cuda")   # contents undefined: no zeroing needed
+    d_sc, d_ln = gpu.to_dev(sc), gpu.to_dev(np.repeat(ln[:, None], Hkv, 1))
+    for _ in range(2):                             # twice on the same workspace
+        keep = torch.full((Bt, Hkv, budget), -1, dtype=torch.int32, device="cuda")
+        fk.fk_select_keep_ws(desc, d_sc, None, d_ln, hint, budget, recent, keep, ws)
+        gpu.assert_keep_equal(keep.cpu().numpy(), ref, ln, budget)
+    keep1 = torch.full((Bt, Hkv, budget), -1, dtype=torch.int32, device="cuda")
+    fk.fk_select_keep(desc, d_sc, None, d_ln, hint, budget, recent, keep1)
+    assert torch.equal(keep1, keep)                # and the one-launch call agrees
+    if nbytes:
+        with pytest.raises(fk.FkError):
+            fk.fk_select_keep_ws(desc, d_sc, None, d_ln, hint, budget, recent, keep, ws[:nbytes - 1])
+
+
+def test_select_keep_ws_on_short_rows_is_the_plain_call(gpu, ora):
+    import paper_2602_03203_amd as fk
+    Bt, Hkv, cap, budget, recent = 16, 8, 2176, 2048, 128
+    desc = fk.CacheDesc(Bt, Hkv, Hkv, 128, cap, "bf16")
+    assert fk.fk_select_keep_workspace(desc, cap, budget, recent) == 0
+    sc = si.gen_scores(31, (Bt, Hkv, cap), ties=2)
+    ln = np.full(Bt, cap, np.int32)
+    ref = ora.select_keep(sc, np.tile(np.arange(cap, dtype=np.int32), (Bt, Hkv, 1)), ln, budget, recent, "sort")
+    keep = torch.full((Bt, Hkv, budget), -1, dtype=torch.int32, device="cuda")
+    fk.fk_select_keep_ws(desc, gpu.to_dev(sc), None, gpu.to_dev(np.repeat(ln[:, None], Hkv, 1)), cap, budget, recent, keep, None)
+    gpu.assert_keep_equal(keep.cpu().numpy(), ref, ln, budget)
+
+
 def test_prepared_call_replays_the_direct_call(gpu, ora):
     """fk.prepare marshals once; the callable it returns makes the same library call each time it is used."""
     import paper_2602_03203_amd as fk
