@@ -379,7 +379,7 @@ static SelPlan select_plan(const fk_cache_desc* d, int max_len, int budget, int 
     SelPlan p = {1, 0, 0, 0};
     const int rows = d->batch * d->n_kv_heads, kmax = budget - recent;
     if (rows > 64 || max_len < 16384 || kmax <= 0) return p;
-    int nchunk = 256 / rows;                                   // about one workgroup per CU
+    int nchunk = 256 / rows;                                   // one workgroup per CU (measured: 128 and 512 are slower)
     const int fit = (kSelMaxLdsKeys / 2) / kmax;               // survivors of all chunks: keys + slots in LDS
     if (nchunk > fit) nchunk = fit;
     if (nchunk > 16) nchunk = 16;  // kMaxChunks of the kernel
