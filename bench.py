@@ -581,9 +581,8 @@ def main():
                 calls.append(fk.prepare(fk.fk_decode_window, desc, dq[t:t + seg], Kc, Vc, posc, lenc, dk[t:t + seg], dv[t:t + seg],
                                         pos_dev[t:t + seg], seg, ml, scale, dout[:seg], ws, stream))
             else:
-                for u in range(t, t + seg):
-                    calls.append(fk.prepare(fk.fk_decode_step_feat, desc, dq[u], Kc, Vc, posc, lenc, dk[u], dv[u], pos_dev[u],
-                                            int(min(lens_at[u].max(), w.capacity)), scale, feat, (c0 + u) % L, L, dout[u - t], fws, stream))
+                calls.append(fk.prepare(fk.fk_decode_window_feat, desc, dq[t:t + seg], Kc, Vc, posc, lenc, dk[t:t + seg], dv[t:t + seg],
+                                        pos_dev[t:t + seg], seg, ml, scale, feat, (c0 + t) % L, L, dout[:seg], fws, stream))
             if rec is not None:
                 calls.append(lambda ev=e[1]: ev.record(stream))
                 rec["attn"].append((t, seg, e))

@@ -260,6 +260,19 @@ fk_status fk_decode_step_feat(const fk_cache_desc *desc, const void *q, void *K,
                               size_t workspace_bytes, void *stream);
 
 /*
+ * Appendix B.1 (the queries of one chunk): n_steps consecutive fk_decode_step_feat calls enqueued by one
+ * call, step t at chunk position chunk_pos_first + t, on q_seq[t], k_seq[t], v_seq[t], pos_seq[t] with its
+ * output in out_seq[t] and max_len = min(max_len_first + t, capacity).  Layouts as for fk_decode_window;
+ * the window must end inside the chunk (chunk_pos_first + n_steps <= chunk_len).  Results are those of
+ * the n_steps single calls.
+ */
+fk_status fk_decode_window_feat(const fk_cache_desc *desc, const void *q_seq, void *K, void *V, int32_t *pos,
+                                int32_t *len, const void *k_seq, const void *v_seq, const int32_t *pos_seq,
+                                int32_t n_steps, int32_t max_len_first, float softmax_scale, float *feat,
+                                int32_t chunk_pos_first, int32_t chunk_len, void *out_seq, void *workspace,
+                                size_t workspace_bytes, void *stream);
+
+/*
  * fk_score_kv on x = concat(k, v, a) (Section 3.1 Eq. 1 with the attention features of Appendix
  * B.1).  scorer->w1 is [n_sets][2*head_dim + 6 g][hidden]; the fp32 features enter the contraction as
  * a bf16 head plus a bf16 remainder (16 significant bits; fp32 caches: plain fp32).  bf16: FK_ERR_UNSUPPORTED

@@ -21,7 +21,7 @@ FK_F32, FK_BF16 = 0, 1
 
 SYMBOLS = ["fk_status_string", "fk_version", "fk_append", "fk_decode_attn_workspace", "fk_decode_attn", "fk_decode_step", "fk_decode_window", "fk_decode_step_static",
            "fk_score_kv", "fk_select_keep", "fk_select_keep_workspace", "fk_select_keep_ws", "fk_select_keep_sampled", "fk_compact", "fk_decode_step_feat_workspace",
-           "fk_decode_step_feat", "fk_score_kv_feat", "fk_compact_feat", "fk_golden_steps", "fk_golden_scores",
+           "fk_decode_step_feat", "fk_decode_window_feat", "fk_score_kv_feat", "fk_compact_feat", "fk_golden_steps", "fk_golden_scores",
            "fk_golden_trace", "fk_stream_read"]
 
 
@@ -69,6 +69,7 @@ def lib() -> ctypes.CDLL:
         L.fk_compact.restype, L.fk_compact.argtypes = ctypes.c_int, [dp, vp, vp, vp, vp, vp, i32, vp]
         L.fk_decode_step_feat_workspace.restype, L.fk_decode_step_feat_workspace.argtypes = sz, [dp]
         L.fk_decode_step_feat.restype, L.fk_decode_step_feat.argtypes = ctypes.c_int, [dp, vp, vp, vp, vp, vp, vp, vp, vp, i32, f32, vp, i32, i32, vp, vp, sz, vp]
+        L.fk_decode_window_feat.restype, L.fk_decode_window_feat.argtypes = ctypes.c_int, [dp, vp, vp, vp, vp, vp, vp, vp, vp, i32, i32, f32, vp, i32, i32, vp, vp, sz, vp]
         L.fk_score_kv_feat.restype, L.fk_score_kv_feat.argtypes = ctypes.c_int, [dp, vp, vp, vp, vp, i32, sp, vp, vp]
         L.fk_compact_feat.restype, L.fk_compact_feat.argtypes = ctypes.c_int, [dp, vp, vp, vp, vp, vp, vp, i32, vp]
         L.fk_golden_steps.restype, L.fk_golden_steps.argtypes = i32, [i32, i32, i32]
@@ -274,6 +275,15 @@ def fk_decode_step_feat(desc: CacheDesc, q, K, V, pos, length, k_new, v_new, pos
                                      _ptr(k_new), _ptr(v_new), _ptr(pos_new), int(max_len), float(softmax_scale),
                                      _ptr(feat), int(chunk_pos), int(chunk_len), _ptr(out), _ptr(workspace), nbytes,
                                      _stream(stream))
+
+
+def fk_decode_window_feat(desc: CacheDesc, q_seq, K, V, pos, length, k_seq, v_seq, pos_seq, n_steps: int, max_len_first: int,
+                          softmax_scale: float, feat, chunk_pos_first: int, chunk_len: int, out_seq, workspace, stream=None) -> None:
+    """n_steps consecutive fk_decode_step_feat calls (chunk positions chunk_pos_first ..) enqueued by one call."""
+    nbytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _call("fk_decode_window_feat", ctypes.byref(desc.c()), _ptr(q_seq), _ptr(K), _ptr(V), _ptr(pos), _ptr(length), _ptr(k_seq),
+          _ptr(v_seq), _ptr(pos_seq), int(n_steps), int(max_len_first), float(softmax_scale), _ptr(feat), int(chunk_pos_first),
+          int(chunk_len), _ptr(out_seq), _ptr(workspace), nbytes, _stream(stream))
 
 
 def fk_score_kv_feat(desc: CacheDesc, K, V, feat, length, max_len: int, W1, b1, W2, b2, scores, stream=None,

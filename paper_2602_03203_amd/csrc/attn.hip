@@ -1022,3 +1022,29 @@ extern "C" fk_status fk_decode_step_feat(const fk_cache_desc* desc, const void* 
     P.chunk_len = chunk_len;
     return attn_entry(desc, P, max_len, softmax_scale, workspace, workspace_bytes, stream);
 }
+
+// fk_decode_step_feat for the steps from chunk_pos_first to the end of a window inside one chunk, enqueued by one call
+extern "C" fk_status fk_decode_window_feat(const fk_cache_desc* desc, const void* q_seq, void* K, void* V, int32_t* pos,
+                                           int32_t* len, const void* k_seq, const void* v_seq, const int32_t* pos_seq,
+                                           int32_t n_steps, int32_t max_len_first, float softmax_scale, float* feat,
+                                           int32_t chunk_pos_first, int32_t chunk_len, void* out_seq, void* workspace,
+                                           size_t workspace_bytes, void* stream) {
+    fk_status s = check_desc(desc);
+    if (s != FK_OK) return s;
+    if (n_steps < 0 || max_len_first <= 0 || max_len_first > desc->capacity) return FK_ERR_INVALID_ARG;
+    if (!q_seq || !k_seq || !v_seq || !pos_seq || !out_seq) return FK_ERR_INVALID_ARG;
+    if (chunk_len <= 0 || chunk_pos_first < 0 || (int64_t)chunk_pos_first + n_steps > chunk_len) return FK_ERR_INVALID_ARG;
+    const size_t e = desc->dtype == FK_F32 ? 4 : 2;
+    const size_t q_step = (size_t)desc->batch * desc->n_q_heads * desc->head_dim * e;   // bytes per step, multiples of 16
+    const size_t kv_step = (size_t)desc->batch * desc->n_kv_heads * desc->head_dim * e;
+    for (int32_t t = 0; t < n_steps; ++t) {
+        const int64_t ml = (int64_t)max_len_first + t;
+        s = fk_decode_step_feat(desc, static_cast<const char*>(q_seq) + t * q_step, K, V, pos, len,
+                                static_cast<const char*>(k_seq) + t * kv_step, static_cast<const char*>(v_seq) + t * kv_step,
+                                pos_seq + (size_t)t * desc->batch, ml > desc->capacity ? desc->capacity : (int32_t)ml,
+                                softmax_scale, feat, chunk_pos_first + t, chunk_len,
+                                static_cast<char*>(out_seq) + t * q_step, workspace, workspace_bytes, stream);
+        if (s != FK_OK) return s;
+    }
+    return FK_OK;
+}

@@ -191,6 +191,39 @@ def test_tiny_workload_full_run_with_features(gpu, ora):
     assert lockstep_feat(gpu, ora, w, w.steps) == 16
 
 
+def test_window_call_equals_the_single_steps(gpu):
+    """fk_decode_window_feat enqueues the same launches as the per-step calls: every buffer ends bit-identical (the
+    per-step path is the one the other tests of this file hold against the oracle)."""
+    import paper_2602_03203_amd as fk
+    Bt, Hq, Hkv, D, cap, L, n0, steps, c0 = 3, 8, 2, 128, 300, 32, 200, 20, 7
+    d = fk.CacheDesc(Bt, Hq, Hkv, D, cap, "bf16")
+    g = torch.Generator(device="cuda").manual_seed(5)
+    mk = lambda *shape: (torch.randn(shape, generator=g, device="cuda") / 8).to(torch.bfloat16)
+    K0, V0 = mk(Bt, Hkv, cap, D), mk(Bt, Hkv, cap, D)
+    q, k, v = mk(steps, Bt, Hq, D), mk(steps, Bt, Hkv, D), mk(steps, Bt, Hkv, D)
+    ps = (torch.arange(steps, dtype=torch.int32, device="cuda")[:, None] + n0).expand(steps, Bt).contiguous()
+    pos0 = torch.arange(cap, dtype=torch.int32, device="cuda").expand(Bt, Hkv, cap).contiguous()
+    feat0 = torch.rand((Bt, Hkv, 6, cap, fk.feat_heads(d)), generator=g, device="cuda")
+    results = []
+    for window in (False, True):
+        K, V, pos, feat = K0.clone(), V0.clone(), pos0.clone(), feat0.clone()
+        ln = torch.full((Bt, Hkv), n0, dtype=torch.int32, device="cuda")
+        out = torch.zeros((steps, Bt, Hq, D), dtype=torch.bfloat16, device="cuda")
+        ws = fk.new_feat_workspace(d)
+        if window:
+            fk.fk_decode_window_feat(d, q, K, V, pos, ln, k, v, ps, steps, n0 + 1, 0.7, feat, c0, L, out, ws)
+        else:
+            for t in range(steps):
+                fk.fk_decode_step_feat(d, q[t], K, V, pos, ln, k[t], v[t], ps[t], n0 + 1 + t, 0.7, feat, c0 + t, L, out[t], ws)
+        torch.cuda.synchronize()
+        results.append((K, V, pos, feat, ln, out))
+    for a, b in zip(*results):
+        assert torch.equal(a.view(torch.uint8) if a.dtype == torch.bfloat16 else a, b.view(torch.uint8) if b.dtype == torch.bfloat16 else b)
+    assert (results[0][4] == n0 + steps).all()
+    with pytest.raises(fk.FkError):   # the window must end inside the chunk
+        fk.fk_decode_window_feat(d, q, K, V, pos, ln, k, v, ps, steps, n0 + 1, 0.7, feat, L - steps + 1, L, out, ws)
+
+
 def test_bad_arguments_are_refused(gpu):
     import paper_2602_03203_amd as fk
     z = torch.zeros(64 * 128 * 4, dtype=torch.bfloat16, device="cuda")
