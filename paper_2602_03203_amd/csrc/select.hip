@@ -13,6 +13,74 @@
 
 namespace fk {
 
+// Four most-significant-digit-first passes over the slots [0, nslots) whose key_of(i, valid) reports valid: finds the
+// key T of the k-th best valid slot and the number `want` of valid slots equal to T that still belong to the k best
+// (1 <= k <= number of valid slots).  hist: [4][256] in LDS, zero on entry (one histogram per pass, one barrier per pass).
+// U keys per thread are fetched before the first of them is used.  Every thread of the workgroup must call this.
+template <int THREADS, int U, typename KeyFn>
+__device__ __forceinline__ void msd_select(KeyFn key_of, int nslots, uint32_t k, uint32_t* hist4, uint32_t* T_out,
+                                           uint32_t* want_out) {
+    const int lane = threadIdx.x & (kWave - 1);
+    uint32_t prefix = 0, mask = 0, want = k;
+    for (int pass = 0; pass < 4; ++pass) {
+        const int shift = 24 - 8 * pass;
+        uint32_t* hist = hist4 + pass * 256;
+        for (int i0 = 0; i0 < nslots; i0 += U * THREADS) {   // uniform trip count: the wavefront votes below
+            uint32_t kv[U];
+            bool ok[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) kv[u] = key_of(min(i0 + u * THREADS + (int)threadIdx.x, nslots - 1), ok[u]);
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const bool todo = ok[u] && i0 + u * THREADS + (int)threadIdx.x < nslots && (kv[u] & mask) == prefix;
+                const uint32_t dg = (kv[u] >> shift) & 0xffu;
+                // Scores of one row share their sign and most of their exponent: in the first pass a wavefront's keys
+                // usually all carry one digit, and 2000 atomics on one LDS word queue up for 3000 cycles.  One vote: if
+                // every pending lane has the first one's digit, one lane adds the count; otherwise one atomic per lane.
+                // (Counting the first few distinct digits of a wavefront this way was measured: slower.)
+                const unsigned long long act = __ballot(todo);
+                if (act != 0) {
+                    const int first = __ffsll((long long)act) - 1;
+                    const uint32_t lead = __builtin_amdgcn_readlane(dg, first);
+                    if (__ballot(todo && dg == lead) == act) {
+                        if (lane == first) atomicAdd(&hist[lead], (uint32_t)__popcll(act));
+                    } else if (todo) {
+                        atomicAdd(&hist[dg], 1u);
+                    }
+                }
+            }
+        }
+        __syncthreads();
+        // Every wavefront finds the digit for itself (no broadcast through LDS, one barrier per pass): lane l owns
+        // digits 255-4l .. 252-4l (descending); the digit where the running count from the top reaches `want`.
+        const uint4 h4 = *reinterpret_cast<const uint4*>(hist + 252 - 4 * lane);
+        const uint32_t c[4] = {h4.w, h4.z, h4.y, h4.x};
+        const uint32_t tot = c[0] + c[1] + c[2] + c[3];
+        const uint32_t incl = wave_scan_incl(tot), excl = incl - tot;
+        uint32_t digit = 0, above = 0;
+        const bool mine = excl < want && want <= incl;  // exactly one lane
+        if (mine) {
+            uint32_t run = excl;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                if (run < want && want <= run + c[j]) {
+                    digit = 255 - 4 * lane - j;
+                    above = run;
+                }
+                run += c[j];
+            }
+        }
+        const int src = __ffsll((long long)__ballot(mine)) - 1;
+        digit = __builtin_amdgcn_readlane(digit, src);
+        above = __builtin_amdgcn_readlane(above, src);
+        prefix |= digit << shift;
+        mask |= 0xffu << shift;
+        want -= above;
+    }
+    *T_out = prefix;
+    *want_out = want;
+}
+
 // LDS: hist [4][256] u32 (one histogram per pass, cleared once) | wavefront totals [16][2] | keys [lds_keys] u32
 static constexpr int kSelMaxLdsKeys = 36 * 1024;  // 144 KB of keys beside the histograms
 // (Four wavefronts per row instead of sixteen were measured and dropped: 11.3 against 8.1 us; the passes are bound by
@@ -112,69 +180,13 @@ __global__ __launch_bounds__(THREADS) void select_keep_kernel(const float* __res
     __syncthreads();
     auto key_at = [&](int i) { return in_lds ? s_key[i] : score_key(sc[i]); };
 
-    // U keys per thread are fetched before the first of them is used (rows read from global memory: 16 loads in flight)
-    auto count_digits = [&](auto u_, uint32_t* hist, uint32_t prefix, uint32_t mask, int shift) {
-        constexpr int U = decltype(u_)::value;
-        for (int i0 = 0; i0 < ncand; i0 += U * THREADS) {   // uniform trip count: the wavefront votes below
-            uint32_t kv[U];
-#pragma unroll
-            for (int u = 0; u < U; ++u) kv[u] = key_at(min(i0 + u * THREADS + (int)threadIdx.x, ncand - 1));
-#pragma unroll
-            for (int u = 0; u < U; ++u) {
-                const bool todo = i0 + u * THREADS + (int)threadIdx.x < ncand && (kv[u] & mask) == prefix;
-                const uint32_t dg = (kv[u] >> shift) & 0xffu;
-                // Scores of one row share their sign and most of their exponent: in the first pass a wavefront's keys
-                // usually all carry one digit, and 2000 atomics on one LDS word queue up for 3000 cycles.  One vote: if
-                // every pending lane has the first one's digit, one lane adds the count; otherwise one atomic per lane.
-                const unsigned long long act = __ballot(todo);
-                if (act != 0) {
-                    const int first = __ffsll((long long)act) - 1;
-                    const uint32_t lead = __builtin_amdgcn_readlane(dg, first);
-                    if (__ballot(todo && dg == lead) == act) {
-                        if (lane == first) atomicAdd(&hist[lead], (uint32_t)__popcll(act));
-                    } else if (todo) {
-                        atomicAdd(&hist[dg], 1u);
-                    }
-                }
-            }
-        }
-    };
-
-    uint32_t prefix = 0, mask = 0;
-    uint32_t want = (uint32_t)k;   // how many still to take among keys matching the prefix
+    // (rows read from global memory: 16 loads in flight per thread)
+    uint32_t prefix = 0;
+    uint32_t want = (uint32_t)k;   // how many still to take among keys equal to the threshold
     if (k > 0) {
-        for (int pass = 0; pass < 4; ++pass) {
-            const int shift = 24 - 8 * pass;
-            uint32_t* hist = s_hist + pass * 256;
-            if (in_lds) count_digits(std::integral_constant<int, 2>{}, hist, prefix, mask, shift);
-            else count_digits(std::integral_constant<int, 16>{}, hist, prefix, mask, shift);
-            __syncthreads();
-            // Every wavefront finds the digit for itself (no broadcast through LDS, one barrier per pass): lane l owns
-            // digits 255-4l .. 252-4l (descending); the digit where the running count from the top reaches `want`.
-            const uint4 h4 = *reinterpret_cast<const uint4*>(hist + 252 - 4 * lane);
-            const uint32_t c[4] = {h4.w, h4.z, h4.y, h4.x};
-            const uint32_t tot = c[0] + c[1] + c[2] + c[3];
-            const uint32_t incl = wave_scan_incl(tot), excl = incl - tot;
-            uint32_t digit = 0, above = 0;
-            const bool mine = excl < want && want <= incl;  // exactly one lane
-            if (mine) {
-                uint32_t run = excl;
-#pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    if (run < want && want <= run + c[j]) {
-                        digit = 255 - 4 * lane - j;
-                        above = run;
-                    }
-                    run += c[j];
-                }
-            }
-            const int src = __ffsll((long long)__ballot(mine)) - 1;
-            digit = __builtin_amdgcn_readlane(digit, src);
-            above = __builtin_amdgcn_readlane(above, src);
-            prefix |= digit << shift;
-            mask |= 0xffu << shift;
-            want -= above;
-        }
+        auto key_of = [&](int i, bool& valid) { valid = true; return key_at(i); };
+        if (in_lds) msd_select<THREADS, 2>(key_of, ncand, (uint32_t)k, s_hist, &prefix, &want);
+        else msd_select<THREADS, 16>(key_of, ncand, (uint32_t)k, s_hist, &prefix, &want);
     }
     // now: keep key > prefix, and the first `want` keys == prefix (k == 0: keep no candidate).  Ordered pass: every
     // wavefront owns one contiguous stretch of the row and walks it 64 slots at a time (coalesced, no barrier inside):
@@ -331,6 +343,138 @@ __global__ __launch_bounds__(kSelThreads) void select_keep_sampled_kernel(const 
     for (int j = threadIdx.x; j < recent; j += kSelThreads) out[budget - recent + j] = others + j;
 }
 
+
+// The same selection with the row in LDS (rows of up to kSampledLdsKeys candidates): both keys of every slot are formed
+// once, the radix passes and the ordered passes are those of select_keep_kernel (one barrier per pass, one ordered
+// walk per wavefront stretch), and the candidate marks take the place of the first key once the safe set is known.
+// LDS: hist [2][4][256] u32 | wavefront totals [16][4] | key1 / candidate mark [lds_keys] | key2 [lds_keys]
+static constexpr int kSampledLdsKeys = 18 * 1024;
+template <int THREADS>
+__global__ __launch_bounds__(THREADS) void select_keep_sampled_lds_kernel(const float* __restrict__ scores,
+                                                                          const float* __restrict__ noise,
+                                                                          const int32_t* __restrict__ len, int cap,
+                                                                          int budget, int recent, int n_cand, int lds_keys,
+                                                                          int32_t* __restrict__ keep) {
+    const int row = blockIdx.x;
+    const int n = min(len[row], cap);
+    int32_t* out = keep + (size_t)row * budget;
+    if (n <= budget) {  // nothing to prune: the identity over the whole row
+        for (int j = threadIdx.x; j < budget; j += THREADS) out[j] = j;
+        return;
+    }
+    const float* sc = scores + (size_t)row * cap;
+    const float* nz = noise + (size_t)row * cap;
+    const int others = n - recent;  // slots [0, others) are not protected (others <= lds_keys: checked on the host)
+    const int E = n - budget;       // pairs to evict (1 <= E <= others)
+    const int K = min(max(n_cand, E), others);  // candidates
+    const int k_safe = others - K;  // most important pairs, never evicted
+    const int k2 = K - E;           // candidates that stay
+
+    extern __shared__ __attribute__((aligned(16))) uint32_t s_sel_mem[];
+    uint32_t* s_hist = s_sel_mem;            // [2][4][256]
+    uint32_t* s_wtot = s_hist + 2 * 4 * 256; // [16][4]
+    uint32_t* s_k1 = s_wtot + 64;            // [lds_keys] key of the score; later 1 = candidate, 0 = safe
+    uint32_t* s_k2 = s_k1 + lds_keys;        // [lds_keys] key of score - noise
+    constexpr int WAVES = THREADS / kWave;
+    const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
+
+    for (int i = threadIdx.x; i < 2 * 4 * 256; i += THREADS) s_hist[i] = 0;
+    for (int i0 = threadIdx.x; i0 < others; i0 += 8 * THREADS) {
+        float v[8], z[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const int i = min(i0 + u * THREADS, others - 1);
+            v[u] = sc[i];
+            z[u] = nz[i];
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u)
+            if (i0 + u * THREADS < others) {
+                s_k1[i0 + u * THREADS] = score_key(v[u]);
+                s_k2[i0 + u * THREADS] = score_key(v[u] - z[u]);
+            }
+    }
+    __syncthreads();
+
+    // every wavefront owns one contiguous stretch of the row (the ordered passes walk it 64 slots at a time)
+    const int stretch = (((others + WAVES - 1) / WAVES) + kWave - 1) / kWave * kWave;
+    const int w0 = min(wave * stretch, others), w1 = min(w0 + stretch, others);
+
+    // (1) safe set: the k_safe best by score; everything else becomes a candidate
+    uint32_t T1 = 0, want1 = 0;
+    if (k_safe > 0)
+        msd_select<THREADS, 2>([&](int i, bool& valid) { valid = true; return s_k1[i]; }, others, (uint32_t)k_safe, s_hist, &T1,
+                               &want1);
+    {
+        uint32_t eq = 0;  // slots equal to T1 in this stretch
+        if (k_safe > 0)
+            for (int i0 = w0; i0 < w1; i0 += kWave) {
+                const int i = i0 + lane;
+                eq += (uint32_t)__popcll(__ballot(i < w1 && s_k1[min(i, others - 1)] == T1));
+            }
+        if (lane == 0) s_wtot[4 * wave] = eq;
+        __syncthreads();
+        uint32_t eq_run = 0;
+        for (int w = 0; w < wave; ++w) eq_run += s_wtot[4 * w];
+        for (int i0 = w0; i0 < w1; i0 += kWave) {
+            const int i = i0 + lane;
+            const bool live = i < w1;
+            const uint32_t key = s_k1[min(i, others - 1)];
+            const bool is_eq = k_safe > 0 && live && key == T1;
+            const unsigned long long me = __ballot(is_eq);
+            const uint32_t e_below = __builtin_amdgcn_mbcnt_hi((uint32_t)(me >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)me, 0));
+            const bool safe = k_safe > 0 && (key > T1 || (is_eq && eq_run + e_below < want1));
+            if (live) s_k1[i] = safe ? 0u : 1u;
+            eq_run += (uint32_t)__popcll(me);
+        }
+    }
+    __syncthreads();
+
+    // (2) which candidates stay: the k2 largest t = score - noise among them
+    uint32_t T2 = 0, want2 = 0;
+    if (k2 > 0)
+        msd_select<THREADS, 2>([&](int i, bool& valid) { valid = s_k1[i] != 0u; return s_k2[i]; }, others, (uint32_t)k2,
+                               s_hist + 4 * 256, &T2, &want2);
+
+    // (3) ordered output: safe pairs, surviving candidates (ties to the lower slot), protected tail
+    auto walk = [&](auto write_, uint32_t& keep_run, uint32_t& eq_run) {
+        constexpr bool WRITE = decltype(write_)::value;
+        for (int i0 = w0; i0 < w1; i0 += kWave) {
+            const int i = i0 + lane;
+            const bool live = i < w1;
+            const int ii = min(i, others - 1);
+            const bool cand = s_k1[ii] != 0u;
+            const uint32_t key = s_k2[ii];
+            const bool sure = live && (!cand || (k2 > 0 && key > T2));   // kept whatever the ties do
+            const bool tie = live && cand && k2 > 0 && key == T2;
+            const unsigned long long ms = __ballot(sure), mt = __ballot(tie);
+            if constexpr (WRITE) {
+                const uint32_t s_below = __builtin_amdgcn_mbcnt_hi((uint32_t)(ms >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)ms, 0));
+                const uint32_t t_below = __builtin_amdgcn_mbcnt_hi((uint32_t)(mt >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)mt, 0));
+                const uint32_t sb = keep_run + s_below, tb = eq_run + t_below;  // kept for sure / tied, before slot i
+                if (sure) out[sb + min(tb, want2)] = i;
+                else if (tie && tb < want2) out[sb + tb] = i;
+            }
+            keep_run += (uint32_t)__popcll(ms);
+            eq_run += (uint32_t)__popcll(mt);
+        }
+    };
+    uint32_t kept = 0, tied = 0;
+    walk(std::false_type{}, kept, tied);
+    if (lane == 0) {
+        s_wtot[4 * wave + 1] = kept;
+        s_wtot[4 * wave + 2] = tied;
+    }
+    __syncthreads();
+    uint32_t kept_before = 0, tied_before = 0;
+    for (int w = 0; w < wave; ++w) {
+        kept_before += s_wtot[4 * w + 1];
+        tied_before += s_wtot[4 * w + 2];
+    }
+    walk(std::true_type{}, kept_before, tied_before);
+    for (int j = threadIdx.x; j < recent; j += THREADS) out[budget - recent + j] = others + j;
+}
+
 }  // namespace fk
 
 using namespace fk;
@@ -446,6 +590,16 @@ extern "C" fk_status fk_select_keep_sampled(const fk_cache_desc* desc, const flo
         return FK_ERR_INVALID_ARG;
     if (desc->capacity > kSampledMaxLen) return FK_ERR_UNSUPPORTED;  // the candidate bitmap covers every slot a row can hold
     const int rows = desc->batch * desc->n_kv_heads;
+    if (desc->capacity <= kSampledLdsKeys) {  // every row fits LDS with both of its keys
+        const int lds_keys = (desc->capacity + 3) & ~3;
+        const size_t lds = sizeof(uint32_t) * (2 * 4 * 256 + 64 + 2 * (size_t)lds_keys);
+        auto kern = select_keep_sampled_lds_kernel<kSelThreads>;
+        static bool lds_ok[kMaxDevices] = {};
+        if (!allow_dynamic_lds((const void*)kern, 160 * 1024, lds_ok)) return FK_ERR_LAUNCH;
+        hipLaunchKernelGGL(kern, dim3(rows), dim3(kSelThreads), lds, (hipStream_t)stream, scores, noise, len, desc->capacity,
+                           budget, protect_recent, n_candidates, lds_keys, keep_idx);
+        return launch_status();
+    }
     hipLaunchKernelGGL(select_keep_sampled_kernel, dim3(rows), dim3(kSelThreads), 0, (hipStream_t)stream, scores,
                        noise, len, desc->capacity, budget, protect_recent, n_candidates, keep_idx);
     return launch_status();
