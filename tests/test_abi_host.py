@@ -103,6 +103,20 @@ def test_argument_validation_of_the_next_row_calls(fklib):
     assert L.fk_score_kv_feat(ctypes.byref(good), p, p, p, p, 512, ctypes.byref(S(p, p, p, p, 44, 1)), p, 0) == fklib.FK_ERR_UNSUPPORTED
     assert L.fk_compact_feat(ctypes.byref(good), p, p, p, 0, p, p, 256, 0) == fklib.FK_ERR_INVALID_ARG
     assert L.fk_compact_feat(ctypes.byref(good), p, p, p, p, p, p, 513, 0) == fklib.FK_ERR_INVALID_ARG
+    # windows of the feature path: the window must end inside the chunk
+    assert L.fk_decode_window_feat(ctypes.byref(good), *args, 4, 512, 1.0, p, 126, 128, p, p, need, 0) == fklib.FK_ERR_INVALID_ARG
+    assert L.fk_decode_window_feat(ctypes.byref(good), *args, 0, 512, 1.0, p, 0, 128, p, p, need, 0) == fklib.FK_OK   # no step: no launch
+    assert L.fk_decode_window_feat(ctypes.byref(good), p, p, p, p, p, 0, p, p, 4, 512, 1.0, p, 0, 128, p, p, need, 0) == fklib.FK_ERR_INVALID_ARG
+    # selection of few long rows: workspace sizes are a host-side plan; a short workspace is refused before any launch
+    long_rows = D(1, 8, 4, 128, 131072, fklib.FK_BF16)
+    ws = L.fk_select_keep_workspace(ctypes.byref(long_rows), 131072, 2048, 128)
+    assert ws >= 4 * 2 * (2048 - 128) * 4                      # at least two chunks of survivors per row
+    assert L.fk_select_keep_workspace(ctypes.byref(good), 512, 256, 32) == 0           # short rows are not split
+    assert L.fk_select_keep_workspace(ctypes.byref(long_rows), 131072, 2048, 2048) == 0   # nothing to select
+    assert L.fk_select_keep_workspace(ctypes.byref(long_rows), 131073, 2048, 128) == 0    # bad arguments
+    assert L.fk_select_keep_ws(ctypes.byref(long_rows), p, p, p, 131072, 2048, 128, p, p, ws - 1, 0) == fklib.FK_ERR_WORKSPACE
+    assert L.fk_select_keep_ws(ctypes.byref(long_rows), p, p, p, 131072, 2048, 128, p, 0, 0, 0) == fklib.FK_ERR_WORKSPACE
+    assert L.fk_select_keep_ws(ctypes.byref(long_rows), p, p, p, 131072, 4096, 5000, p, p, ws, 0) == fklib.FK_ERR_INVALID_ARG
     # Golden Eviction
     assert L.fk_golden_steps(8192, 2048, 128) == 47 and L.fk_golden_steps(2176, 2048, 128) == 0
     assert L.fk_golden_steps(0, 2048, 128) == -1 and L.fk_golden_steps(100, 8, 16) == -1
