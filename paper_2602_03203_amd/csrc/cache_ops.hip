@@ -44,28 +44,20 @@ static constexpr int kCompactThreads = 1024;
 static constexpr int kCompactU = 4;     // 16-byte loads in flight per thread
 static constexpr int kSliceChunks = 8;  // 16-byte chunks per column slice
 
-// CLAMP: the workgroup that moves the positions also sets len[row] = min(len[row], budget) (no second launch).
-// No other workgroup may then read len[row]: what moves is decided by keep alone (rows at or under budget carry
-// the identity, entries with keep[j] == j or outside [0, cap) move nothing).  Without CLAMP len[row] is read by
-// every workgroup (rows at or under budget return at once, sources are checked against len) and left alone.
-template <bool CLAMP>
+// The workgroup that moves the positions also sets len[row] = min(len[row], budget) (no second launch).  No other
+// workgroup may then read len[row]: what moves is decided by keep alone (rows at or under budget carry the
+// identity, entries with keep[j] == j or outside [0, cap) move nothing).
 __global__ __launch_bounds__(kCompactThreads) void compact_kernel(uint4* __restrict__ K, uint4* __restrict__ V,
                                                                   int32_t* __restrict__ pos,
                                                                   int32_t* __restrict__ len,
                                                                   const int32_t* __restrict__ keep,
                                                                   int cap, int budget, int chunks) {
     const int row = blockIdx.x;
-    int n = cap;
-    if constexpr (!CLAMP) {
-        n = min(len[row], cap);
-        if (n <= budget) return;
-    }
+    const int n = cap;
     const int32_t* kp = keep + (size_t)row * budget;
     const int slices = chunks / kSliceChunks;
     if ((int)blockIdx.y == 2 * slices) {
-        if constexpr (CLAMP) {
-            if (threadIdx.x == 0 && len[row] > budget) len[row] = budget;
-        }
+        if (threadIdx.x == 0 && len[row] > budget) len[row] = budget;
         int32_t* p = pos + (size_t)row * cap;
         for (int base = 0; base < budget; base += kCompactThreads * kCompactU) {
             int32_t val[kCompactU];
@@ -163,12 +155,6 @@ __global__ __launch_bounds__(kCompactThreads) void feat_roll_kernel(float4* __re
     }
 }
 
-// after every row has been compacted: len[row] = min(len[row], budget)
-__global__ void clamp_len_kernel(int32_t* __restrict__ len, int rows, int budget) {
-    const int r = blockIdx.x * blockDim.x + threadIdx.x;
-    if (r < rows && len[r] > budget) len[r] = budget;
-}
-
 }  // namespace fk
 
 using namespace fk;
@@ -196,7 +182,7 @@ extern "C" fk_status fk_compact(const fk_cache_desc* desc, void* K, void* V, int
     const int chunks = desc->head_dim * (desc->dtype == FK_F32 ? 4 : 2) / 16;
     const int rows = desc->batch * desc->n_kv_heads;
     hipStream_t st = (hipStream_t)stream;
-    hipLaunchKernelGGL(compact_kernel<true>, dim3(rows, 2 * (chunks / kSliceChunks) + 1), dim3(kCompactThreads), 0, st, (uint4*)K, (uint4*)V,
+    hipLaunchKernelGGL(compact_kernel, dim3(rows, 2 * (chunks / kSliceChunks) + 1), dim3(kCompactThreads), 0, st, (uint4*)K, (uint4*)V,
                        pos, len, keep_idx, desc->capacity, budget, chunks);
     return launch_status();
 }
@@ -212,14 +198,14 @@ extern "C" fk_status fk_compact_feat(const fk_cache_desc* desc, void* K, void* V
     const int rows = desc->batch * desc->n_kv_heads;
     const int g = desc->n_q_heads / desc->n_kv_heads;
     hipStream_t st = (hipStream_t)stream;
-    hipLaunchKernelGGL(compact_kernel<false>, dim3(rows, 2 * (chunks / kSliceChunks) + 1), dim3(kCompactThreads), 0, st, (uint4*)K, (uint4*)V,
-                       pos, len, keep_idx, desc->capacity, budget, chunks);
+    // the features first: their kernel needs the lengths as they were; the cache's compaction then clamps them
     if (g <= 4)
         hipLaunchKernelGGL(feat_roll_kernel<1>, dim3(rows), dim3(kCompactThreads), 0, st, (float4*)feat, len, keep_idx,
                            desc->capacity, budget);
     else
         hipLaunchKernelGGL(feat_roll_kernel<2>, dim3(rows), dim3(kCompactThreads), 0, st, (float4*)feat, len, keep_idx,
                            desc->capacity, budget);
-    hipLaunchKernelGGL(clamp_len_kernel, dim3((rows + 255) / 256), dim3(256), 0, st, len, rows, budget);
+    hipLaunchKernelGGL(compact_kernel, dim3(rows, 2 * (chunks / kSliceChunks) + 1), dim3(kCompactThreads), 0, st, (uint4*)K, (uint4*)V,
+                       pos, len, keep_idx, desc->capacity, budget, chunks);
     return launch_status();
 }
