@@ -630,6 +630,11 @@ def main():
         run(W_steps, clock0_w, lens_at_w, dp_w)
     torch.cuda.synchronize()
     reset(len0)
+    # The reset rewrote the caches; three untimed attention passes WITHOUT append (they change nothing) bring them to
+    # where a running generation has them (this layer's K and V last touched by an attention launch) and the clocks up.
+    ml0 = int(min(lens0.max(), w.capacity))
+    for _ in range(3):
+        fk.fk_decode_attn(desc, dq[0], Kc, Vc, lenc, ml0, scale, dout[0], ws, stream)
     torch.cuda.synchronize()
     done = torch.cuda.Event()
     timed_calls = plan(K_steps, clock0, lens_at, dp)   # marshalled before the clock starts
