@@ -212,13 +212,16 @@ def bench_golden(args):
     entries = Hq * sum(q + 1 for q in range(B + L, T))          # causal entries of the pooled queries
     e0 = [torch.cuda.Event(enable_timing=True) for _ in range(K_steps)]
     e1 = [torch.cuda.Event(enable_timing=True) for _ in range(K_steps)]
+    e2 = [torch.cuda.Event(enable_timing=True) for _ in range(K_steps)]
     for i in range(K_steps):
         e0[i].record(stream)
         fk.fk_golden_scores(A, Hkv, T, B, L, a_t, alpha, stream)
         e1[i].record(stream)
         fk.fk_golden_trace(alpha, T, B, L, kept, stream)
+        e2[i].record(stream)
     torch.cuda.synchronize()
     ms = float(np.mean([a.elapsed_time(b) for a, b in zip(e0, e1)]))
+    ms_trace = float(np.mean([a.elapsed_time(b) for a, b in zip(e1, e2)]))
     bytes_alg = entries * 2 + 2 * Hkv * M * T * 4 * 2           # A once; block scores written, read, future scores written
     achieved = bytes_alg / (ms * 1e-3) / 1e9
     result = {
@@ -232,6 +235,8 @@ def bench_golden(args):
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
                      "traffic": profile_value("golden_pool_kernel_qwen3_4b_8k_trace.txt", "traffic_bytes_per_launch"),
                      "avg_launch_us": ms * 1e3, "algorithmic_bytes_per_launch": bytes_alg},
+        "trace": {"kernel": "golden_trace_kernel (fk_golden_trace): M sequential selections, one workgroup per KV group",
+                  "us": ms_trace * 1e3, "us_per_step": ms_trace * 1e3 / M},
     }
     if not args.no_cpu:
         from oracle import golden

@@ -93,62 +93,103 @@ __global__ void golden_future_kernel(const float* __restrict__ a_tilde, int Tn, 
     }
 }
 
-static constexpr int kTraceMaxCache = 12288;  // B + L positions (48 KB) + B keys in LDS
+static constexpr int kTraceMaxCache = 12288;  // B + L positions and B keys in LDS (96 KB)
 
-// one workgroup per KV group; the cache (positions, ascending) lives in LDS
+// One workgroup per KV group.  LDS holds the cache's positions (ascending; B + L of them: the B of this step and the
+// L that are generated before the next one) and the keys of its first B entries under this step's future scores.
+// A step: (1) the loads of the NEXT step's future scores at every position that can still be a candidate then are
+// issued (they land while the step selects); (2) four radix passes find the key of the (B - L)-th best candidate;
+// (3) every wavefront walks its own contiguous stretch of the candidates, first to count its survivors, then, with
+// the counts of the stretches before it, to move them (position and next key) to the front in order.  Sources are
+// in registers before the barrier that precedes the moves, so the compaction is safe in place.
+// PER_LANE: candidates one lane holds (stretch of a wavefront / 64) and newest pairs one thread holds (L / 1024), at most.
+template <int PER_LANE>
 __global__ __launch_bounds__(kSelThreads) void golden_trace_kernel(const float* __restrict__ alpha, int Tn, int M,
                                                                    int budget, int L, int32_t* __restrict__ kept) {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     int32_t* s_pos = reinterpret_cast<int32_t*>(smem);                 // [budget + L]
     uint32_t* s_key = reinterpret_cast<uint32_t*>(s_pos + budget + L);  // [budget]
-    __shared__ uint32_t s_hist[256];
-    __shared__ uint32_t s_sel[2];
-    __shared__ unsigned long long s_part[kSelWaves];
-    const int hp = blockIdx.x;
+    __shared__ __attribute__((aligned(16))) uint32_t s_hist[4 * 256];
+    __shared__ uint32_t s_wtot[2 * kSelWaves];
+    static_assert(kSelThreads == 4 * 256, "one thread clears one histogram word");
+    const int hp = blockIdx.x, lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
     const int k = budget - L;  // old pairs that stay
+    const float* al = alpha + (size_t)hp * M * Tn;
     for (int j = threadIdx.x; j < budget + L; j += kSelThreads) s_pos[j] = j;
+    for (int j = threadIdx.x; j < budget; j += kSelThreads) s_key[j] = score_key(al[j]);
+    s_hist[threadIdx.x] = 0;
     __syncthreads();
+    const int stretch = ((budget + kSelWaves - 1) / kSelWaves + kWave - 1) / kWave * kWave;  // <= 64 * PER_LANE (host)
+    const int w0 = min(wave * stretch, budget), w1 = min(w0 + stretch, budget);
     for (int t = 1; t <= M; ++t) {
-        const float* al = alpha + ((size_t)hp * M + (t - 1)) * Tn;
         int32_t* out = kept + ((size_t)hp * M + (t - 1)) * budget;
-        for (int j = threadIdx.x; j < budget; j += kSelThreads) s_key[j] = score_key(al[s_pos[j]]);
-        __syncthreads();
-        uint32_t Tk = 0, want = 0;
-        if (k > 0)
-            radix_threshold(budget, (uint32_t)k, [&](int i, bool& valid) { valid = true; return s_key[i]; }, s_hist, s_sel,
-                            &Tk, &want);
-        // ordered pass: survivors move to the front of the cache, in order (destination <= source, and every
-        // source of a chunk is read before the barriers inside the scan, so the move is safe in place)
-        uint32_t gt_base = 0, eq_base = 0;
-        for (int base = 0; base < budget; base += kSelThreads) {
-            const int i = base + threadIdx.x;
-            uint32_t gt = 0, eq = 0;
-            int32_t p = 0;
-            if (i < budget && k > 0) {
-                const uint32_t key = s_key[i];
-                gt = key > Tk;
-                eq = key == Tk;
-                p = s_pos[i];
-            }
-            unsigned long long tot;
-            const unsigned long long incl = block_scan_incl(((unsigned long long)gt << 32) | eq, s_part, &tot);
-            const uint32_t gt_before = gt_base + (uint32_t)(incl >> 32) - gt;
-            const uint32_t eq_before = eq_base + (uint32_t)(incl & 0xffffffffu) - eq;
-            if (gt || (eq && eq_before < want)) {
-                const uint32_t dst = gt_before + min(eq_before, want);
-                s_pos[dst] = p;
-                out[dst] = p;
-            }
-            gt_base += (uint32_t)(tot >> 32);
-            eq_base += (uint32_t)(tot & 0xffffffffu);
+        const bool more = t < M;
+        const float* aln = al + (size_t)t * Tn;   // future scores of step t + 1
+        const int new0 = budget + (t - 1) * L;   // first of the L newest pairs (they stay)
+        float nxt[PER_LANE], nxt_new[PER_LANE];
+#pragma unroll
+        for (int u = 0; u < PER_LANE; ++u) {
+            const int i = w0 + u * kWave + lane, j = (int)threadIdx.x + u * kSelThreads;
+            nxt[u] = more && i < w1 ? aln[s_pos[i]] : 0.f;
+            nxt_new[u] = more && j < L ? aln[new0 + j] : 0.f;
         }
-        __syncthreads();
+        uint32_t Tk = 0, want = 0, gt = 0, eq = 0;
+        uint32_t kv[PER_LANE];
+        int32_t pv[PER_LANE];
+        if (k > 0) {
+            msd_select<kSelThreads, 2>([&](int i, bool& valid) { valid = true; return s_key[i]; }, budget, (uint32_t)k, s_hist,
+                                       &Tk, &want);
+#pragma unroll
+            for (int u = 0; u < PER_LANE; ++u) {
+                const int i = w0 + u * kWave + lane;
+                const bool live = i < w1;
+                kv[u] = live ? s_key[i] : 0u;
+                pv[u] = live ? s_pos[i] : 0;
+                gt += (uint32_t)__popcll(__ballot(live && kv[u] > Tk));
+                eq += (uint32_t)__popcll(__ballot(live && kv[u] == Tk));
+            }
+            if (lane == 0) {
+                s_wtot[2 * wave] = gt;
+                s_wtot[2 * wave + 1] = eq;
+            }
+        }
+        __syncthreads();  // every source is in registers, the counts are visible, the histograms have been read
+        s_hist[threadIdx.x] = 0;
+        if (k > 0) {
+            uint32_t gt_run = 0, eq_run = 0;
+            for (int w = 0; w < wave; ++w) {
+                gt_run += s_wtot[2 * w];
+                eq_run += s_wtot[2 * w + 1];
+            }
+#pragma unroll
+            for (int u = 0; u < PER_LANE; ++u) {
+                const int i = w0 + u * kWave + lane;
+                const bool live = i < w1;
+                const unsigned long long mg = __ballot(live && kv[u] > Tk), me = __ballot(live && kv[u] == Tk);
+                const uint32_t gb = gt_run + __builtin_amdgcn_mbcnt_hi((uint32_t)(mg >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)mg, 0));
+                const uint32_t eb = eq_run + __builtin_amdgcn_mbcnt_hi((uint32_t)(me >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)me, 0));
+                const bool keep = live && (kv[u] > Tk || (kv[u] == Tk && eb < want));
+                if (keep) {
+                    const uint32_t dst = gb + min(eb, want);
+                    s_pos[dst] = pv[u];
+                    s_key[dst] = score_key(nxt[u]);
+                    out[dst] = pv[u];
+                }
+                gt_run += (uint32_t)__popcll(mg);
+                eq_run += (uint32_t)__popcll(me);
+            }
+        }
         // the L newest stay; then the L pairs generated before the next step join
-        for (int j = threadIdx.x; j < L; j += kSelThreads) {
-            const int32_t p = budget + t * L - L + j;
-            out[k + j] = p;
+#pragma unroll
+        for (int u = 0; u < PER_LANE; ++u) {
+            const int j = (int)threadIdx.x + u * kSelThreads;
+            if (j < L) {
+                out[k + j] = new0 + j;
+                s_pos[k + j] = new0 + j;
+                s_key[k + j] = score_key(nxt_new[u]);
+                s_pos[k + L + j] = new0 + L + j;
+            }
         }
-        for (int j = threadIdx.x; j < 2 * L; j += kSelThreads) s_pos[k + j] = budget + t * L - L + j;
         __syncthreads();
     }
 }
@@ -201,9 +242,16 @@ extern "C" fk_status fk_golden_trace(const float* alpha, int32_t n_kv_heads, int
     const int M = golden_steps(T, budget, interval);
     if (M == 0) return FK_OK;
     const size_t lds = sizeof(int32_t) * ((size_t)budget + interval) + sizeof(uint32_t) * (size_t)budget;
-    static bool lds_ok[kMaxDevices] = {};
-    if (!allow_dynamic_lds((const void*)golden_trace_kernel, sizeof(int32_t) * 2 * kTraceMaxCache, lds_ok)) return FK_ERR_LAUNCH;
-    hipLaunchKernelGGL(golden_trace_kernel, dim3(n_kv_heads), dim3(kSelThreads), lds, (hipStream_t)stream, alpha, T, M,
-                       budget, interval, kept);
-    return launch_status();
+    // candidates per lane: a wavefront's stretch is the budget over the 16 wavefronts, rounded up to whole 64s
+    const int per_lane = ((budget + kSelWaves - 1) / kSelWaves + kWave - 1) / kWave;
+    auto launch = [&](auto kern, bool (&lds_ok)[kMaxDevices]) -> fk_status {
+        if (!allow_dynamic_lds((const void*)kern, sizeof(int32_t) * 2 * kTraceMaxCache, lds_ok)) return FK_ERR_LAUNCH;
+        hipLaunchKernelGGL(kern, dim3(n_kv_heads), dim3(kSelThreads), lds, (hipStream_t)stream, alpha, T, M, budget, interval,
+                           kept);
+        return launch_status();
+    };
+    static bool ok2[kMaxDevices] = {}, ok4[kMaxDevices] = {}, ok12[kMaxDevices] = {};
+    if (per_lane <= 2) return launch(golden_trace_kernel<2>, ok2);
+    if (per_lane <= 4) return launch(golden_trace_kernel<4>, ok4);
+    return launch(golden_trace_kernel<12>, ok12);   // budget + interval <= kTraceMaxCache: at most 12
 }

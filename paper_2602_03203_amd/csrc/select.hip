@@ -13,74 +13,6 @@
 
 namespace fk {
 
-// Four most-significant-digit-first passes over the slots [0, nslots) whose key_of(i, valid) reports valid: finds the
-// key T of the k-th best valid slot and the number `want` of valid slots equal to T that still belong to the k best
-// (1 <= k <= number of valid slots).  hist: [4][256] in LDS, zero on entry (one histogram per pass, one barrier per pass).
-// U keys per thread are fetched before the first of them is used.  Every thread of the workgroup must call this.
-template <int THREADS, int U, typename KeyFn>
-__device__ __forceinline__ void msd_select(KeyFn key_of, int nslots, uint32_t k, uint32_t* hist4, uint32_t* T_out,
-                                           uint32_t* want_out) {
-    const int lane = threadIdx.x & (kWave - 1);
-    uint32_t prefix = 0, mask = 0, want = k;
-    for (int pass = 0; pass < 4; ++pass) {
-        const int shift = 24 - 8 * pass;
-        uint32_t* hist = hist4 + pass * 256;
-        for (int i0 = 0; i0 < nslots; i0 += U * THREADS) {   // uniform trip count: the wavefront votes below
-            uint32_t kv[U];
-            bool ok[U];
-#pragma unroll
-            for (int u = 0; u < U; ++u) kv[u] = key_of(min(i0 + u * THREADS + (int)threadIdx.x, nslots - 1), ok[u]);
-#pragma unroll
-            for (int u = 0; u < U; ++u) {
-                const bool todo = ok[u] && i0 + u * THREADS + (int)threadIdx.x < nslots && (kv[u] & mask) == prefix;
-                const uint32_t dg = (kv[u] >> shift) & 0xffu;
-                // Scores of one row share their sign and most of their exponent: in the first pass a wavefront's keys
-                // usually all carry one digit, and 2000 atomics on one LDS word queue up for 3000 cycles.  One vote: if
-                // every pending lane has the first one's digit, one lane adds the count; otherwise one atomic per lane.
-                // (Counting the first few distinct digits of a wavefront this way was measured: slower.)
-                const unsigned long long act = __ballot(todo);
-                if (act != 0) {
-                    const int first = __ffsll((long long)act) - 1;
-                    const uint32_t lead = __builtin_amdgcn_readlane(dg, first);
-                    if (__ballot(todo && dg == lead) == act) {
-                        if (lane == first) atomicAdd(&hist[lead], (uint32_t)__popcll(act));
-                    } else if (todo) {
-                        atomicAdd(&hist[dg], 1u);
-                    }
-                }
-            }
-        }
-        __syncthreads();
-        // Every wavefront finds the digit for itself (no broadcast through LDS, one barrier per pass): lane l owns
-        // digits 255-4l .. 252-4l (descending); the digit where the running count from the top reaches `want`.
-        const uint4 h4 = *reinterpret_cast<const uint4*>(hist + 252 - 4 * lane);
-        const uint32_t c[4] = {h4.w, h4.z, h4.y, h4.x};
-        const uint32_t tot = c[0] + c[1] + c[2] + c[3];
-        const uint32_t incl = wave_scan_incl(tot), excl = incl - tot;
-        uint32_t digit = 0, above = 0;
-        const bool mine = excl < want && want <= incl;  // exactly one lane
-        if (mine) {
-            uint32_t run = excl;
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                if (run < want && want <= run + c[j]) {
-                    digit = 255 - 4 * lane - j;
-                    above = run;
-                }
-                run += c[j];
-            }
-        }
-        const int src = __ffsll((long long)__ballot(mine)) - 1;
-        digit = __builtin_amdgcn_readlane(digit, src);
-        above = __builtin_amdgcn_readlane(above, src);
-        prefix |= digit << shift;
-        mask |= 0xffu << shift;
-        want -= above;
-    }
-    *T_out = prefix;
-    *want_out = want;
-}
-
 // LDS: hist [4][256] u32 (one histogram per pass, cleared once) | wavefront totals [16][2] | keys [lds_keys] u32
 static constexpr int kSelMaxLdsKeys = 36 * 1024;  // 144 KB of keys beside the histograms
 // (Four wavefronts per row instead of sixteen were measured and dropped: 11.3 against 8.1 us; the passes are bound by

@@ -112,5 +112,109 @@ __device__ __forceinline__ void radix_threshold(int nslots, uint32_t k, KeyFn ke
     *want_out = want;
 }
 
+// Most-significant-digit-first passes (8-bit digits, at most four) over the slots [0, nslots) whose key_of(i, valid)
+// reports valid: finds the key T of the k-th best valid slot and the number `want` of valid slots equal to T that
+// still belong to the k best (1 <= k <= number of valid slots).  hist: [4][256] in LDS, zero on entry, dirty on return
+// (one histogram per pass, one barrier per pass).  U keys per thread are fetched before the first of them is used.
+// Every thread of the workgroup must call this.
+//
+// Early finish: once the digit's bin holds at most 64 slots, no further histogram is built.  One sweep appends the
+// remaining bits of those slots to a list (in the last pass's histogram, which is then never needed), and every
+// wavefront ranks the list by itself, one entry per lane: entries are made distinct by their list index, the entry of
+// rank want - 1 carries the threshold.  The list's order depends on the order of the atomics; the threshold and the
+// count above it do not.  Scores spread over a binade or more take two histograms and the list instead of four
+// histograms; rows of equal scores still take four.
+template <int THREADS, int U, typename KeyFn>
+__device__ __forceinline__ void msd_select(KeyFn key_of, int nslots, uint32_t k, uint32_t* hist4, uint32_t* T_out,
+                                           uint32_t* want_out) {
+    const int lane = threadIdx.x & (kWave - 1);
+    uint32_t prefix = 0, mask = 0, want = k;
+    for (int pass = 0; pass < 4; ++pass) {
+        const int shift = 24 - 8 * pass;
+        uint32_t* hist = hist4 + pass * 256;
+        for (int i0 = 0; i0 < nslots; i0 += U * THREADS) {   // uniform trip count: the wavefront votes below
+            uint32_t kv[U];
+            bool ok[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) kv[u] = key_of(min(i0 + u * THREADS + (int)threadIdx.x, nslots - 1), ok[u]);
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const bool todo = ok[u] && i0 + u * THREADS + (int)threadIdx.x < nslots && (kv[u] & mask) == prefix;
+                const uint32_t dg = (kv[u] >> shift) & 0xffu;
+                // Scores of one row share their sign and most of their exponent: in the first pass a wavefront's keys
+                // usually all carry one digit, and atomics of many lanes on one LDS word are served one per cycle (2000
+                // keys on one word: 2000 cycles).  One vote: if every pending lane has the first one's digit, one lane
+                // adds the count; otherwise one atomic per lane.  (Measured and dropped: counting the first lane's digit
+                // by vote also when the wavefront is not unanimous, and peeling several digits off it one vote each;
+                // the votes' scalar round trips cost what the shorter queues save, or more.)
+                const unsigned long long act = __ballot(todo);
+                if (act != 0) {
+                    const int first = __ffsll((long long)act) - 1;
+                    const uint32_t lead = __builtin_amdgcn_readlane(dg, first);
+                    if (__ballot(todo && dg == lead) == act) {
+                        if (lane == first) atomicAdd(&hist[lead], (uint32_t)__popcll(act));
+                    } else if (todo) {
+                        atomicAdd(&hist[dg], 1u);
+                    }
+                }
+            }
+        }
+        __syncthreads();
+        // Every wavefront finds the digit for itself (no broadcast through LDS, one barrier per pass): lane l owns
+        // digits 255-4l .. 252-4l (descending); the digit where the running count from the top reaches `want`.
+        const uint4 h4 = *reinterpret_cast<const uint4*>(hist + 252 - 4 * lane);
+        const uint32_t c[4] = {h4.w, h4.z, h4.y, h4.x};
+        const uint32_t tot = c[0] + c[1] + c[2] + c[3];
+        const uint32_t incl = wave_scan_incl(tot), excl = incl - tot;
+        uint32_t digit = 0, above = 0, inbin = 0;
+        const bool mine = excl < want && want <= incl;  // exactly one lane
+        if (mine) {
+            uint32_t run = excl;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                if (run < want && want <= run + c[j]) {
+                    digit = 255 - 4 * lane - j;
+                    above = run;
+                    inbin = c[j];
+                }
+                run += c[j];
+            }
+        }
+        const int src = __ffsll((long long)__ballot(mine)) - 1;
+        digit = __builtin_amdgcn_readlane(digit, src);
+        above = __builtin_amdgcn_readlane(above, src);
+        inbin = __builtin_amdgcn_readlane(inbin, src);
+        prefix |= digit << shift;
+        mask |= 0xffu << shift;
+        want -= above;   // 1 <= want <= inbin
+        if (pass < 3 && inbin <= (uint32_t)kWave) {   // the same for every wavefront: all read the same histogram
+            uint32_t* fill = hist4 + 3 * 256;   // the last pass's histogram, still zero: [0] entries so far, [1 + i] entry i
+            for (int i0 = 0; i0 < nslots; i0 += U * THREADS) {
+                uint32_t kv[U];
+                bool ok[U];
+#pragma unroll
+                for (int u = 0; u < U; ++u) kv[u] = key_of(min(i0 + u * THREADS + (int)threadIdx.x, nslots - 1), ok[u]);
+#pragma unroll
+                for (int u = 0; u < U; ++u)
+                    if (ok[u] && i0 + u * THREADS + (int)threadIdx.x < nslots && (kv[u] & mask) == prefix)
+                        fill[1 + atomicAdd(fill, 1u)] = kv[u] & ~mask;
+            }
+            __syncthreads();
+            const bool have = (uint32_t)lane < inbin;
+            const uint32_t low = have ? fill[1 + lane] : 0u;                    // at most 24 bits
+            const uint32_t tag = have ? ((low << 6) | (uint32_t)(63 - lane)) + 1u : 0u;  // distinct, 0 = no entry
+            uint32_t rank = 0;
+            for (uint32_t j = 0; j < inbin; ++j) rank += __builtin_amdgcn_readlane(tag, j) > tag;
+            const int at = __ffsll((long long)__ballot(have && rank == want - 1)) - 1;   // exactly one lane
+            const uint32_t tlow = __builtin_amdgcn_readlane(low, at);
+            *T_out = prefix | tlow;
+            *want_out = want - (uint32_t)__popcll(__ballot(have && low > tlow));
+            return;
+        }
+    }
+    *T_out = prefix;
+    *want_out = want;
+}
+
 }  // namespace fk
 #endif

@@ -110,6 +110,25 @@ def test_exact_ties_keep_the_lower_position(gpu):
         assert np.array_equal(kept[0, t - 1], np.concatenate([np.arange(B - L), np.arange(B + t * L - L, B + t * L)]))
 
 
+@pytest.mark.parametrize("Hkv,T,B,L", [
+    (2, 16000, 9000, 1100),   # a wavefront's stretch of candidates is 9 x 64 wide, more than 1024 newest pairs per step
+    (1, 9000, 4096, 512),     # stretches of exactly 4 x 64
+    (3, 5000, 2049, 7),       # one candidate beyond two full stretches per lane
+])
+def test_trace_on_large_budgets(gpu, Hkv, T, B, L):
+    """The trace alone on synthetic future scores (random, with repeated values so that ties at the cut occur):
+    budgets whose candidates span many slots per lane.  Bit exact against the oracle's trace."""
+    import paper_2602_03203_amd as fk
+    from oracle import golden
+    M = golden.n_steps(T, B, L)
+    rng = np.random.default_rng(T + B + L)
+    alpha = (rng.integers(0, 4096, size=(Hkv, M, T)) / 4096.0).astype(np.float32)
+    print(f"trace Hkv={Hkv} T={T} B={B} L={L} M={M}", flush=True)
+    d_kept = torch.full((Hkv, M, B), -1, dtype=torch.int32, device="cuda")
+    fk.fk_golden_trace(torch.from_numpy(alpha).cuda(), T, B, L, d_kept)
+    assert np.array_equal(d_kept.cpu().numpy(), golden.trace(alpha, B, L))
+
+
 def test_layer_slice_at_paper_budget(gpu):
     """Budget 256, L 64 on a 2048-token trace, 8 query heads in 2 groups, bf16: 27 steps, tiles on and
     off the diagonal, every output compared."""

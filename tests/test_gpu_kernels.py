@@ -232,6 +232,36 @@ def test_select_keep_bit_exact(gpu, ora, Bt, Hkv, cap, lens, budget, recent, tie
     gpu.assert_keep_equal(keep.cpu().numpy(), ref, ln, budget)
 
 
+@pytest.mark.parametrize("cluster,dup", [(1, 0), (2, 1), (33, 0), (63, 1), (64, 0), (64, 1), (65, 0), (65, 1), (200, 1)])
+@pytest.mark.parametrize("gap_bits", [0, 9, 15])
+def test_select_keep_threshold_inside_a_small_cluster(gpu, ora, cluster, dup, gap_bits):
+    """The cut falls inside a cluster of scores that share their leading bits (1 + j * 2^(gap_bits - 23), all in
+    [1, 2)); 500 scores lie above it in [2, 4), the rest below in [0.25, 0.5).  Clusters of at most 64 are resolved by
+    ranking a list, larger ones by further histograms.  With dup the cluster holds every value twice (ties at the cut go
+    to the lower position)."""
+    import paper_2602_03203_amd as fk
+    cap, recent, others = 900, 50, 500
+    rng = np.random.default_rng(cluster * 100 + dup * 10 + gap_bits)
+    sc = np.empty((1, 2, cap), np.float32)
+    for h in range(2):
+        row = (0.25 + 0.25 * rng.random(cap)).astype(np.float32)
+        slots = rng.permutation(cap - recent)
+        row[slots[:others]] = (2.0 + 2.0 * rng.random(others)).astype(np.float32)
+        j = np.arange(cluster) // 2 if dup else np.arange(cluster)
+        row[slots[others:others + cluster]] = (1.0 + (j << gap_bits) * 2.0 ** -23).astype(np.float32)
+        sc[0, h] = row
+        mid = sc[0, h, : cap - recent]
+        assert ((mid >= 1.0) & (mid < 2.0)).sum() == cluster and (mid >= 2.0).sum() == others
+    budget = others + (cluster + 1) // 2 + recent                           # the cut lies in the middle of the cluster
+    pos = np.tile(np.arange(cap, dtype=np.int32), (1, 2, 1))
+    ln = np.array([cap], np.int32)
+    ref = ora.select_keep(sc, pos, ln, budget, recent, "sort")
+    desc = fk.CacheDesc(1, 2, 2, 128, cap, "bf16")
+    keep = torch.full((1, 2, budget), -1, dtype=torch.int32, device="cuda")
+    fk.fk_select_keep(desc, gpu.to_dev(sc), None, gpu.to_dev(np.repeat(ln[:, None], 2, 1)), cap, budget, recent, keep)
+    gpu.assert_keep_equal(keep.cpu().numpy(), ref, ln, budget)
+
+
 SPLIT_SELECT_CASES = [
     # Bt, Hkv, cap, lens, max_len hint, budget, recent, ties -- few long rows: fk_select_keep_ws cuts them into chunks
     (1, 4, 131072, [131072], 131072, 2048, 128, 0),            # the one-shot benchmark's row: 9 chunks
