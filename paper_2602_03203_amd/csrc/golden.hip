@@ -111,12 +111,22 @@ __global__ __launch_bounds__(kSelThreads) void golden_trace_kernel(const float* 
     uint32_t* s_key = reinterpret_cast<uint32_t*>(s_pos + budget + L);  // [budget]
     __shared__ __attribute__((aligned(16))) uint32_t s_hist[4 * 256];
     __shared__ uint32_t s_wtot[2 * kSelWaves];
+    __shared__ uint32_t s_wor[kSelWaves];   // every wavefront's OR of key ^ base over the keys it wrote for the next step
     static_assert(kSelThreads == 4 * 256, "one thread clears one histogram word");
     const int hp = blockIdx.x, lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
     const int k = budget - L;  // old pairs that stay
     const float* al = alpha + (size_t)hp * M * Tn;
     for (int j = threadIdx.x; j < budget + L; j += kSelThreads) s_pos[j] = j;
-    for (int j = threadIdx.x; j < budget; j += kSelThreads) s_key[j] = score_key(al[j]);
+    // base, spread: one of the step's keys and the bits in which any of them differs from it (the select starts at
+    // the highest such bit); the spread of the next step's keys is gathered while they are written
+    uint32_t base = score_key(al[0]), spread = 0;
+    for (int j = threadIdx.x; j < budget; j += kSelThreads) {
+        const uint32_t key = score_key(al[j]);
+        s_key[j] = key;
+        spread |= key ^ base;
+    }
+    spread = wave_or(spread);
+    if (lane == 0) s_wor[wave] = spread;
     s_hist[threadIdx.x] = 0;
     __syncthreads();
     const int stretch = ((budget + kSelWaves - 1) / kSelWaves + kWave - 1) / kWave * kWave;  // <= 64 * PER_LANE (host)
@@ -126,6 +136,10 @@ __global__ __launch_bounds__(kSelThreads) void golden_trace_kernel(const float* 
         const bool more = t < M;
         const float* aln = al + (size_t)t * Tn;   // future scores of step t + 1
         const int new0 = budget + (t - 1) * L;   // first of the L newest pairs (they stay)
+        uint32_t diff = 0;
+#pragma unroll
+        for (int w = 0; w < kSelWaves; ++w) diff |= s_wor[w];
+        const uint32_t base_next = more ? score_key(aln[new0]) : 0u;
         float nxt[PER_LANE], nxt_new[PER_LANE];
 #pragma unroll
         for (int u = 0; u < PER_LANE; ++u) {
@@ -138,7 +152,7 @@ __global__ __launch_bounds__(kSelThreads) void golden_trace_kernel(const float* 
         int32_t pv[PER_LANE];
         if (k > 0) {
             msd_select<kSelThreads, 2>([&](int i, bool& valid) { valid = true; return s_key[i]; }, budget, (uint32_t)k, s_hist,
-                                       &Tk, &want);
+                                       base, diff, &Tk, &want);
 #pragma unroll
             for (int u = 0; u < PER_LANE; ++u) {
                 const int i = w0 + u * kWave + lane;
@@ -155,6 +169,7 @@ __global__ __launch_bounds__(kSelThreads) void golden_trace_kernel(const float* 
         }
         __syncthreads();  // every source is in registers, the counts are visible, the histograms have been read
         s_hist[threadIdx.x] = 0;
+        spread = 0;
         if (k > 0) {
             uint32_t gt_run = 0, eq_run = 0;
             for (int w = 0; w < wave; ++w) {
@@ -171,8 +186,10 @@ __global__ __launch_bounds__(kSelThreads) void golden_trace_kernel(const float* 
                 const bool keep = live && (kv[u] > Tk || (kv[u] == Tk && eb < want));
                 if (keep) {
                     const uint32_t dst = gb + min(eb, want);
+                    const uint32_t key = score_key(nxt[u]);
                     s_pos[dst] = pv[u];
-                    s_key[dst] = score_key(nxt[u]);
+                    s_key[dst] = key;
+                    spread |= key ^ base_next;
                     out[dst] = pv[u];
                 }
                 gt_run += (uint32_t)__popcll(mg);
@@ -186,10 +203,15 @@ __global__ __launch_bounds__(kSelThreads) void golden_trace_kernel(const float* 
             if (j < L) {
                 out[k + j] = new0 + j;
                 s_pos[k + j] = new0 + j;
-                s_key[k + j] = score_key(nxt_new[u]);
+                const uint32_t key = score_key(nxt_new[u]);
+                s_key[k + j] = key;
+                spread |= key ^ base_next;
                 s_pos[k + L + j] = new0 + L + j;
             }
         }
+        spread = wave_or(spread);
+        if (lane == 0) s_wor[wave] = spread;
+        base = base_next;
         __syncthreads();
     }
 }

@@ -13,8 +13,10 @@
 
 namespace fk {
 
-// LDS: hist [4][256] u32 (one histogram per pass, cleared once) | wavefront totals [16][2] | keys [lds_keys] u32
+// LDS: hist [4][256] u32 (one histogram per pass, cleared once) | wavefront totals [16][2] | wavefront ORs [16] |
+// keys [lds_keys] u32
 static constexpr int kSelMaxLdsKeys = 36 * 1024;  // 144 KB of keys beside the histograms
+static constexpr int kSelLdsHead = 4 * 256 + 32 + 16;  // words before the keys: histograms, wavefront counts, wavefront ORs
 // (Four wavefronts per row instead of sixteen were measured and dropped: 11.3 against 8.1 us; the passes are bound by
 // the latency of the key -> atomic -> barrier -> scan chain, not by instruction issue.)
 //
@@ -54,7 +56,8 @@ __global__ __launch_bounds__(THREADS) void select_keep_kernel(const float* __res
     extern __shared__ __attribute__((aligned(16))) uint32_t s_sel_mem[];
     uint32_t* s_hist = s_sel_mem;                 // [4][256]
     uint32_t* s_wtot = s_hist + 4 * 256;          // [16][2]: kept counts of every wavefront (greater, equal)
-    uint32_t* s_key = s_wtot + 32;                // [lds_keys]
+    uint32_t* s_wor = s_wtot + 32;                // [16]: every wavefront's OR of key ^ first key
+    uint32_t* s_key = s_wor + 16;                 // [lds_keys]
     uint32_t* s_slot = s_key + lds_keys;          // kSelMerge: [lds_keys] the candidates' slots
     constexpr int WAVES = THREADS / kWave;
     const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
@@ -85,6 +88,7 @@ __global__ __launch_bounds__(THREADS) void select_keep_kernel(const float* __res
     // The row's keys are read from global memory once and kept in LDS (rows beyond the LDS share of the launch are
     // re-read from global memory in every pass).  Eight loads in flight per thread.
     const bool in_lds = ncand <= lds_keys;  // kSelMerge: the host sized the launch so that it is
+    uint32_t base = 0, diff = ~0u;          // the keys' common bits, where known (msd_select)
     for (int i = threadIdx.x; i < 4 * 256; i += THREADS) s_hist[i] = 0;
     if constexpr (MODE == kSelMerge) {
 #pragma unroll
@@ -100,16 +104,31 @@ __global__ __launch_bounds__(THREADS) void select_keep_kernel(const float* __res
             }
         }
     } else if (in_lds) {
+        // on the way: which bits differ between any two keys of the row (the select starts at the highest of them)
+        base = score_key(sc[0]);
+        uint32_t spread = 0;
         for (int i0 = threadIdx.x; i0 < ncand; i0 += 8 * THREADS) {
             float v[8];
 #pragma unroll
             for (int u = 0; u < 8; ++u) v[u] = sc[min(i0 + u * THREADS, ncand - 1)];
 #pragma unroll
-            for (int u = 0; u < 8; ++u)
-                if (i0 + u * THREADS < ncand) s_key[i0 + u * THREADS] = score_key(v[u]);
+            for (int u = 0; u < 8; ++u) {
+                if (i0 + u * THREADS < ncand) {
+                    const uint32_t key = score_key(v[u]);
+                    s_key[i0 + u * THREADS] = key;
+                    spread |= key ^ base;
+                }
+            }
         }
+        spread = wave_or(spread);
+        if (lane == 0) s_wor[wave] = spread;
     }
     __syncthreads();
+    if (MODE != kSelMerge && in_lds) {
+        diff = 0;
+#pragma unroll
+        for (int w = 0; w < WAVES; ++w) diff |= s_wor[w];
+    }
     auto key_at = [&](int i) { return in_lds ? s_key[i] : score_key(sc[i]); };
 
     // (rows read from global memory: 16 loads in flight per thread)
@@ -117,8 +136,8 @@ __global__ __launch_bounds__(THREADS) void select_keep_kernel(const float* __res
     uint32_t want = (uint32_t)k;   // how many still to take among keys equal to the threshold
     if (k > 0) {
         auto key_of = [&](int i, bool& valid) { valid = true; return key_at(i); };
-        if (in_lds) msd_select<THREADS, 2>(key_of, ncand, (uint32_t)k, s_hist, &prefix, &want);
-        else msd_select<THREADS, 16>(key_of, ncand, (uint32_t)k, s_hist, &prefix, &want);
+        if (in_lds) msd_select<THREADS, 2>(key_of, ncand, (uint32_t)k, s_hist, base, diff, &prefix, &want);
+        else msd_select<THREADS, 16>(key_of, ncand, (uint32_t)k, s_hist, base, diff, &prefix, &want);
     }
     // now: keep key > prefix, and the first `want` keys == prefix (k == 0: keep no candidate).  Ordered pass: every
     // wavefront owns one contiguous stretch of the row and walks it 64 slots at a time (coalesced, no barrier inside):
@@ -335,7 +354,7 @@ __global__ __launch_bounds__(THREADS) void select_keep_sampled_lds_kernel(const 
     // (1) safe set: the k_safe best by score; everything else becomes a candidate
     uint32_t T1 = 0, want1 = 0;
     if (k_safe > 0)
-        msd_select<THREADS, 2>([&](int i, bool& valid) { valid = true; return s_k1[i]; }, others, (uint32_t)k_safe, s_hist, &T1,
+        msd_select<THREADS, 2>([&](int i, bool& valid) { valid = true; return s_k1[i]; }, others, (uint32_t)k_safe, s_hist, 0u, ~0u, &T1,
                                &want1);
     {
         uint32_t eq = 0;  // slots equal to T1 in this stretch
@@ -366,7 +385,7 @@ __global__ __launch_bounds__(THREADS) void select_keep_sampled_lds_kernel(const 
     uint32_t T2 = 0, want2 = 0;
     if (k2 > 0)
         msd_select<THREADS, 2>([&](int i, bool& valid) { valid = s_k1[i] != 0u; return s_k2[i]; }, others, (uint32_t)k2,
-                               s_hist + 4 * 256, &T2, &want2);
+                               s_hist + 4 * 256, 0u, ~0u, &T2, &want2);
 
     // (3) ordered output: safe pairs, surviving candidates (ties to the lower slot), protected tail
     auto walk = [&](auto write_, uint32_t& keep_run, uint32_t& eq_run) {
@@ -427,7 +446,7 @@ static fk_status select_whole(const fk_cache_desc* desc, const float* scores, co
     const int rows = desc->batch * desc->n_kv_heads;
     // LDS share for the keys: rows up to max_len keys (the hint) live in LDS; longer ones are read from global memory
     const int lds_keys = ((max_len < kSelMaxLdsKeys ? max_len : kSelMaxLdsKeys) + 3) & ~3;
-    const size_t lds = sizeof(uint32_t) * (4 * 256 + 32 + (size_t)lds_keys);
+    const size_t lds = sizeof(uint32_t) * (kSelLdsHead + (size_t)lds_keys);
     auto kern = select_keep_kernel<kSelThreads, kSelWhole>;
     static bool lds_ok[kMaxDevices] = {};
     if (!allow_dynamic_lds((const void*)kern, 160 * 1024, lds_ok)) return FK_ERR_LAUNCH;
@@ -490,7 +509,7 @@ extern "C" fk_status fk_select_keep_ws(const fk_cache_desc* desc, const float* s
     {
         auto kern = select_keep_kernel<kSelThreads, kSelChunk>;
         const int lds_keys = ((p.chunk_len < kSelMaxLdsKeys ? p.chunk_len : kSelMaxLdsKeys) + 3) & ~3;
-        const size_t lds = sizeof(uint32_t) * (4 * 256 + 32 + (size_t)lds_keys);
+        const size_t lds = sizeof(uint32_t) * (kSelLdsHead + (size_t)lds_keys);
         static bool lds_ok[kMaxDevices] = {};
         if (!allow_dynamic_lds((const void*)kern, 160 * 1024, lds_ok)) return FK_ERR_LAUNCH;
         hipLaunchKernelGGL(kern, dim3(rows * p.nchunk), dim3(kSelThreads), lds, st, scores, len, desc->capacity, budget,
@@ -500,7 +519,7 @@ extern "C" fk_status fk_select_keep_ws(const fk_cache_desc* desc, const float* s
     {
         auto kern = select_keep_kernel<kSelThreads, kSelMerge>;
         const int lds_keys = (p.nchunk * kmax + 3) & ~3;  // <= kSelMaxLdsKeys / 2 by the plan
-        const size_t lds = sizeof(uint32_t) * (4 * 256 + 32 + 2 * (size_t)lds_keys);
+        const size_t lds = sizeof(uint32_t) * (kSelLdsHead + 2 * (size_t)lds_keys);
         static bool lds_ok[kMaxDevices] = {};
         if (!allow_dynamic_lds((const void*)kern, 160 * 1024, lds_ok)) return FK_ERR_LAUNCH;
         hipLaunchKernelGGL(kern, dim3(rows), dim3(kSelThreads), lds, st, scores, len, desc->capacity, budget, protect_recent,

@@ -112,25 +112,48 @@ __device__ __forceinline__ void radix_threshold(int nslots, uint32_t k, KeyFn ke
     *want_out = want;
 }
 
+// OR over the wavefront (result in every lane).
+__device__ __forceinline__ uint32_t wave_or(uint32_t v) {
+    v |= dpp_u32<0x111, 0xF>(v);  // row_shr:1
+    v |= dpp_u32<0x112, 0xF>(v);  // row_shr:2
+    v |= dpp_u32<0x114, 0xF>(v);  // row_shr:4
+    v |= dpp_u32<0x118, 0xF>(v);  // row_shr:8
+    v |= dpp_u32<0x142, 0xA>(v);  // row_bcast:15 into rows 1 and 3
+    v |= dpp_u32<0x143, 0xC>(v);  // row_bcast:31 into rows 2 and 3
+    return (uint32_t)__builtin_amdgcn_readlane((int)v, kWave - 1);
+}
+
 // Most-significant-digit-first passes (8-bit digits, at most four) over the slots [0, nslots) whose key_of(i, valid)
 // reports valid: finds the key T of the k-th best valid slot and the number `want` of valid slots equal to T that
 // still belong to the k best (1 <= k <= number of valid slots).  hist: [4][256] in LDS, zero on entry, dirty on return
 // (one histogram per pass, one barrier per pass).  U keys per thread are fetched before the first of them is used.
-// Every thread of the workgroup must call this.
+// Every thread of the workgroup must call this, with the same arguments.
+//
+// base, diff: what the caller knows about the keys' spread: every valid key agrees with `base` in every bit that is
+// clear in `diff` (base = any valid key, diff = OR over the valid keys of key ^ base; base 0, diff ~0 if unknown).  The
+// first digit starts at the highest bit set in diff: scores of one row share their sign and most of their exponent,
+// so that the 256 bins of the first pass divide the range the keys really cover, not the whole float range.
 //
 // Early finish: once the digit's bin holds at most 64 slots, no further histogram is built.  One sweep appends the
 // remaining bits of those slots to a list (in the last pass's histogram, which is then never needed), and every
 // wavefront ranks the list by itself, one entry per lane: entries are made distinct by their list index, the entry of
 // rank want - 1 carries the threshold.  The list's order depends on the order of the atomics; the threshold and the
-// count above it do not.  Scores spread over a binade or more take two histograms and the list instead of four
-// histograms; rows of equal scores still take four.
+// count above it do not.  With the spread known, 2000 distinct scores mostly take one histogram and the list; rows of
+// equal scores take none (diff 0) or, if a few differ, up to four.
 template <int THREADS, int U, typename KeyFn>
-__device__ __forceinline__ void msd_select(KeyFn key_of, int nslots, uint32_t k, uint32_t* hist4, uint32_t* T_out,
-                                           uint32_t* want_out) {
+__device__ __forceinline__ void msd_select(KeyFn key_of, int nslots, uint32_t k, uint32_t* hist4, uint32_t base,
+                                           uint32_t diff, uint32_t* T_out, uint32_t* want_out) {
     const int lane = threadIdx.x & (kWave - 1);
-    uint32_t prefix = 0, mask = 0, want = k;
-    for (int pass = 0; pass < 4; ++pass) {
-        const int shift = 24 - 8 * pass;
+    if (diff == 0) {   // every valid key is `base`
+        *T_out = base;
+        *want_out = k;
+        return;
+    }
+    int open = 32 - __clz(diff);   // bits [0, open) are still undecided
+    uint32_t mask = open >= 32 ? 0u : ~0u << open, prefix = base & mask, want = k;
+    for (int pass = 0; pass < 4; ++pass) {   // open <= 32 - 8 * pass
+        const int shift = max(open - 8, 0);
+        const uint32_t dmask = (1u << (open - shift)) - 1u;   // eight bits; fewer in a last, short digit
         uint32_t* hist = hist4 + pass * 256;
         for (int i0 = 0; i0 < nslots; i0 += U * THREADS) {   // uniform trip count: the wavefront votes below
             uint32_t kv[U];
@@ -140,7 +163,7 @@ __device__ __forceinline__ void msd_select(KeyFn key_of, int nslots, uint32_t k,
 #pragma unroll
             for (int u = 0; u < U; ++u) {
                 const bool todo = ok[u] && i0 + u * THREADS + (int)threadIdx.x < nslots && (kv[u] & mask) == prefix;
-                const uint32_t dg = (kv[u] >> shift) & 0xffu;
+                const uint32_t dg = (kv[u] >> shift) & dmask;
                 // Scores of one row share their sign and most of their exponent: in the first pass a wavefront's keys
                 // usually all carry one digit, and atomics of many lanes on one LDS word are served one per cycle (2000
                 // keys on one word: 2000 cycles).  One vote: if every pending lane has the first one's digit, one lane
@@ -185,26 +208,40 @@ __device__ __forceinline__ void msd_select(KeyFn key_of, int nslots, uint32_t k,
         above = __builtin_amdgcn_readlane(above, src);
         inbin = __builtin_amdgcn_readlane(inbin, src);
         prefix |= digit << shift;
-        mask |= 0xffu << shift;
+        mask |= dmask << shift;
         want -= above;   // 1 <= want <= inbin
-        if (pass < 3 && inbin <= (uint32_t)kWave) {   // the same for every wavefront: all read the same histogram
-            uint32_t* fill = hist4 + 3 * 256;   // the last pass's histogram, still zero: [0] entries so far, [1 + i] entry i
+        open = shift;
+        if (open == 0) break;   // every bit is decided (after the fourth pass at the latest)
+        if (inbin <= (uint32_t)kWave) {   // the same for every wavefront: all read the same histogram; pass <= 2 here
+            // the last pass's histogram, still zero: [0] entries so far, [4 + i] entry i as a tag: the open bits of the
+            // key above six bits that tell equal keys apart, plus one (0 = no entry)
+            uint32_t* fill = hist4 + 3 * 256;
             for (int i0 = 0; i0 < nslots; i0 += U * THREADS) {
                 uint32_t kv[U];
                 bool ok[U];
 #pragma unroll
                 for (int u = 0; u < U; ++u) kv[u] = key_of(min(i0 + u * THREADS + (int)threadIdx.x, nslots - 1), ok[u]);
 #pragma unroll
-                for (int u = 0; u < U; ++u)
-                    if (ok[u] && i0 + u * THREADS + (int)threadIdx.x < nslots && (kv[u] & mask) == prefix)
-                        fill[1 + atomicAdd(fill, 1u)] = kv[u] & ~mask;
+                for (int u = 0; u < U; ++u) {
+                    if (ok[u] && i0 + u * THREADS + (int)threadIdx.x < nslots && (kv[u] & mask) == prefix) {
+                        const uint32_t idx = atomicAdd(fill, 1u);
+                        fill[4 + idx] = (((kv[u] & ~mask) << 6) | (63u - idx)) + 1u;   // at most 24 open bits
+                    }
+                }
             }
             __syncthreads();
             const bool have = (uint32_t)lane < inbin;
-            const uint32_t low = have ? fill[1 + lane] : 0u;                    // at most 24 bits
-            const uint32_t tag = have ? ((low << 6) | (uint32_t)(63 - lane)) + 1u : 0u;  // distinct, 0 = no entry
+            const uint32_t tag = fill[4 + lane];   // 0 beyond the list
+            const uint32_t low = (tag - 1u) >> 6;
+            // rank = entries with a larger tag; the list is read 16 entries at a time, every lane the same words
             uint32_t rank = 0;
-            for (uint32_t j = 0; j < inbin; ++j) rank += __builtin_amdgcn_readlane(tag, j) > tag;
+            for (uint32_t c = 0; c < inbin; c += 16) {
+                uint4 e[4];
+#pragma unroll
+                for (int q = 0; q < 4; ++q) e[q] = *reinterpret_cast<const uint4*>(fill + 4 + c + 4 * q);
+#pragma unroll
+                for (int q = 0; q < 4; ++q) rank += (e[q].x > tag) + (e[q].y > tag) + (e[q].z > tag) + (e[q].w > tag);
+            }
             const int at = __ffsll((long long)__ballot(have && rank == want - 1)) - 1;   // exactly one lane
             const uint32_t tlow = __builtin_amdgcn_readlane(low, at);
             *T_out = prefix | tlow;
