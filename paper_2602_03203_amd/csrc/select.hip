@@ -298,7 +298,8 @@ __global__ __launch_bounds__(kSelThreads) void select_keep_sampled_kernel(const 
 // The same selection with the row in LDS (rows of up to kSampledLdsKeys candidates): both keys of every slot are formed
 // once, the radix passes and the ordered passes are those of select_keep_kernel (one barrier per pass, one ordered
 // walk per wavefront stretch), and the candidate marks take the place of the first key once the safe set is known.
-// LDS: hist [2][4][256] u32 | wavefront totals [16][4] | key1 / candidate mark [lds_keys] | key2 [lds_keys]
+// LDS: hist [2][4][256] u32 | wavefront totals [16][4] | wavefront ORs [2][16] | key1 / candidate mark [lds_keys] |
+// key2 [lds_keys]
 static constexpr int kSampledLdsKeys = 18 * 1024;
 template <int THREADS>
 __global__ __launch_bounds__(THREADS) void select_keep_sampled_lds_kernel(const float* __restrict__ scores,
@@ -324,12 +325,16 @@ __global__ __launch_bounds__(THREADS) void select_keep_sampled_lds_kernel(const 
     extern __shared__ __attribute__((aligned(16))) uint32_t s_sel_mem[];
     uint32_t* s_hist = s_sel_mem;            // [2][4][256]
     uint32_t* s_wtot = s_hist + 2 * 4 * 256; // [16][4]
-    uint32_t* s_k1 = s_wtot + 64;            // [lds_keys] key of the score; later 1 = candidate, 0 = safe
+    uint32_t* s_wor = s_wtot + 64;           // [2][16] every wavefront's OR of key ^ first key, for either key
+    uint32_t* s_k1 = s_wor + 32;             // [lds_keys] key of the score; later 1 = candidate, 0 = safe
     uint32_t* s_k2 = s_k1 + lds_keys;        // [lds_keys] key of score - noise
     constexpr int WAVES = THREADS / kWave;
     const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
 
     for (int i = threadIdx.x; i < 2 * 4 * 256; i += THREADS) s_hist[i] = 0;
+    // on the way: the bits in which any two keys of the row differ (either select starts at the highest of them)
+    const uint32_t base1 = score_key(sc[0]), base2 = score_key(sc[0] - nz[0]);
+    uint32_t spread1 = 0, spread2 = 0;
     for (int i0 = threadIdx.x; i0 < others; i0 += 8 * THREADS) {
         float v[8], z[8];
 #pragma unroll
@@ -341,11 +346,26 @@ __global__ __launch_bounds__(THREADS) void select_keep_sampled_lds_kernel(const 
 #pragma unroll
         for (int u = 0; u < 8; ++u)
             if (i0 + u * THREADS < others) {
-                s_k1[i0 + u * THREADS] = score_key(v[u]);
-                s_k2[i0 + u * THREADS] = score_key(v[u] - z[u]);
+                const uint32_t key1 = score_key(v[u]), key2 = score_key(v[u] - z[u]);
+                s_k1[i0 + u * THREADS] = key1;
+                s_k2[i0 + u * THREADS] = key2;
+                spread1 |= key1 ^ base1;
+                spread2 |= key2 ^ base2;
             }
     }
+    spread1 = wave_or(spread1);
+    spread2 = wave_or(spread2);
+    if (lane == 0) {
+        s_wor[wave] = spread1;
+        s_wor[16 + wave] = spread2;
+    }
     __syncthreads();
+    uint32_t diff1 = 0, diff2 = 0;
+#pragma unroll
+    for (int w = 0; w < WAVES; ++w) {
+        diff1 |= s_wor[w];
+        diff2 |= s_wor[16 + w];
+    }
 
     // every wavefront owns one contiguous stretch of the row (the ordered passes walk it 64 slots at a time)
     const int stretch = (((others + WAVES - 1) / WAVES) + kWave - 1) / kWave * kWave;
@@ -354,7 +374,7 @@ __global__ __launch_bounds__(THREADS) void select_keep_sampled_lds_kernel(const 
     // (1) safe set: the k_safe best by score; everything else becomes a candidate
     uint32_t T1 = 0, want1 = 0;
     if (k_safe > 0)
-        msd_select<THREADS, 2>([&](int i, bool& valid) { valid = true; return s_k1[i]; }, others, (uint32_t)k_safe, s_hist, 0u, ~0u, &T1,
+        msd_select<THREADS, 2>([&](int i, bool& valid) { valid = true; return s_k1[i]; }, others, (uint32_t)k_safe, s_hist, base1, diff1, &T1,
                                &want1);
     {
         uint32_t eq = 0;  // slots equal to T1 in this stretch
@@ -385,7 +405,7 @@ __global__ __launch_bounds__(THREADS) void select_keep_sampled_lds_kernel(const 
     uint32_t T2 = 0, want2 = 0;
     if (k2 > 0)
         msd_select<THREADS, 2>([&](int i, bool& valid) { valid = s_k1[i] != 0u; return s_k2[i]; }, others, (uint32_t)k2,
-                               s_hist + 4 * 256, 0u, ~0u, &T2, &want2);
+                               s_hist + 4 * 256, base2, diff2, &T2, &want2);
 
     // (3) ordered output: safe pairs, surviving candidates (ties to the lower slot), protected tail
     auto walk = [&](auto write_, uint32_t& keep_run, uint32_t& eq_run) {
@@ -543,7 +563,7 @@ extern "C" fk_status fk_select_keep_sampled(const fk_cache_desc* desc, const flo
     const int rows = desc->batch * desc->n_kv_heads;
     if (desc->capacity <= kSampledLdsKeys) {  // every row fits LDS with both of its keys
         const int lds_keys = (desc->capacity + 3) & ~3;
-        const size_t lds = sizeof(uint32_t) * (2 * 4 * 256 + 64 + 2 * (size_t)lds_keys);
+        const size_t lds = sizeof(uint32_t) * (2 * 4 * 256 + 64 + 32 + 2 * (size_t)lds_keys);
         auto kern = select_keep_sampled_lds_kernel<kSelThreads>;
         static bool lds_ok[kMaxDevices] = {};
         if (!allow_dynamic_lds((const void*)kern, 160 * 1024, lds_ok)) return FK_ERR_LAUNCH;
