@@ -11,7 +11,7 @@
 // workgroup instruction, four instructions in flight per thread); tiles wholly above the diagonal are
 // never read (A is causal), so the traffic is the lower triangle below query B + L.  future is a
 // running maximum down the block axis; trace is sequential by nature: one workgroup per group walks the
-// M steps with the radix select of fk_select_keep on keys gathered into LDS.
+// M steps with the radix select of fk_select_keep on keys in LDS (the next step's are loaded while a step selects).
 #include "select_common.h"
 
 namespace fk {

@@ -3,9 +3,10 @@
 // sampling ablation).
 //
 // One workgroup per row.  Scores are read once, mapped to order-preserving 32-bit keys (larger key =
-// more important; -0 -> +0; NaN -> 0, below -inf) and kept in LDS.  Four most-significant-digit-first passes
-// over 8-bit digits (LDS histograms, one barrier per pass) find the key T of the k-th best candidate and the
-// number `take` of candidates equal to T that still fit.  One ordered pass then writes the kept slots
+// more important; -0 -> +0; NaN -> 0, below -inf) and kept in LDS.  Most-significant-digit-first passes over
+// 8-bit digits (LDS histograms, one barrier per pass; at most four, usually one and a short ranked list: see
+// msd_select) find the key T of the k-th best candidate and the number `take` of candidates equal to T that still
+// fit.  One ordered pass then writes the kept slots
 // ascending: every candidate above T, the first `take` candidates equal to T in slot order
 // (slot order is position order, so ties go to the lower position), and the protected tail.
 #include "select_common.h"
@@ -17,8 +18,8 @@ namespace fk {
 // keys [lds_keys] u32
 static constexpr int kSelMaxLdsKeys = 36 * 1024;  // 144 KB of keys beside the histograms
 static constexpr int kSelLdsHead = 4 * 256 + 32 + 16;  // words before the keys: histograms, wavefront counts, wavefront ORs
-// (Four wavefronts per row instead of sixteen were measured and dropped: 11.3 against 8.1 us; the passes are bound by
-// the latency of the key -> atomic -> barrier -> scan chain, not by instruction issue.)
+// (Four wavefronts per row instead of sixteen were measured and dropped: 11.3 against 8.1 us; a pass is a chain
+// key -> atomic -> barrier -> scan of LDS round trips, which more wavefronts shorten.)
 //
 // Long rows of a small batch (one-shot compression of a long prompt: 32 rows of 131072 pairs) would leave most of the
 // chip idle with one workgroup per row, and their keys do not fit LDS.  fk_select_keep_ws splits such rows (two launches,
